@@ -1,0 +1,292 @@
+/*
+ * kvblade.h -- C ABI of the MI355X-native KV-cache offloading hot path.
+ *
+ * The library maps every per-layer K or V tensor to a contiguous, sector-aligned LBA extent,
+ * marshals KV between the GPU's attention-side layout and extent byte order (pack on offload,
+ * unpack on reload), moves extents between HBM and an LBA-addressed host region in chunks, and
+ * runs split-K decode attention over the reloaded tensors.
+ *
+ * Conventions
+ *  - Every function returns an int: KV_OK (0) or a negative KV_E* code.  Nothing throws or aborts.
+ *  - "host" / "device" is stated for every pointer.  The library never takes ownership of a caller
+ *    buffer.  Streams are hipStream_t passed as void* (NULL = the default stream).
+ *  - Elements are 16-bit (fp16 or bf16); e = 2 bytes.  A tensor id is n = 2*layer + kind with
+ *    KV_K = 0 before KV_V = 1, layers ascending (the id chain of Sec. IV-B "LBA Bind").
+ *  - The storage tier is modelled: the direct path's namespace is a pinned host region whose byte
+ *    offset is LBA * sector_bytes (region base = LBA 0); the page-cache path's files are byte
+ *    offsets in one pageable host arena.
+ */
+#ifndef KVBLADE_H
+#define KVBLADE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- return codes ---- */
+#define KV_OK 0
+#define KV_EINVAL (-1) /* bad argument, dtype, shape, pointer kind */
+#define KV_EALIGN (-2) /* an offset or size that must be a sector multiple is not */
+#define KV_ERANGE (-3) /* token range, layer, sequence or buffer offset outside its bounds */
+#define KV_ENOSPC (-4) /* LBA region, pageable arena, staging or workspace too small */
+#define KV_EHIP (-5)   /* a HIP call failed; see kv_last_hip_error() */
+
+#define KV_F16 0
+#define KV_BF16 1
+
+#define KV_TOKEN_MAJOR 0 /* one extent (S_cap, B*H, D) per tensor; uniform batch */
+#define KV_PER_SEQ 1     /* per tensor: sub-extents (cap_b, H, D), each padded to a sector */
+
+#define KV_PATH_DIRECT 0    /* Group 2: LBA extent in the pinned region */
+#define KV_PATH_PAGECACHE 1 /* Group 1: byte range in the pageable arena */
+
+#define KV_K 0
+#define KV_V 1
+
+#define KV_LAYOUT_BHSD 0  /* strided [B, H, S_alloc, D], d contiguous */
+#define KV_LAYOUT_PAGED 1 /* block pool [n_pool, H, block_tokens, D] + block table */
+
+#define KV_SEQ_ALL (-1)
+#define KV_UNBOUNDED UINT64_MAX
+
+#define KV_OUT_F32 0
+#define KV_OUT_SAME 1 /* fp16 / bf16 as the plan's dtype, round to nearest even */
+
+#define KV_DIR_OFFLOAD 0     /* pack -> D2H (-> memcpy into the arena) */
+#define KV_DIR_RELOAD 1      /* (arena -> memcpy ->) H2D -> unpack */
+#define KV_DIR_RELOAD_ATTN 2 /* RELOAD plus decode attention of each layer */
+
+typedef struct kv_plan kv_plan_t; /* opaque; immutable after creation */
+
+/*
+ * Input of kv_layout_plan.  Alg. 1 (residency) needs L, the size of one K or V tensor and the
+ * knob X; Eq. 3-6 (LBA bind) need the tensor byte size, the LBA size and the user-given first
+ * start LBA.
+ */
+typedef struct kv_plan_desc {
+    int32_t n_layers;     /* L >= 1 */
+    int32_t n_kv_heads;   /* H >= 1 */
+    int32_t n_q_heads;    /* H_q, a multiple of H */
+    int32_t head_dim;     /* D; D*2 must be a multiple of 16 bytes */
+    int32_t batch;        /* B >= 1 */
+    int32_t dtype;        /* KV_F16 | KV_BF16 */
+    int32_t sector_bytes; /* LBA size: 512 or 4096 */
+    int32_t chunk_tokens; /* C: default token rows per chunk; C*row_bytes must be a sector multiple */
+    int32_t extent_mode;  /* KV_TOKEN_MAJOR | KV_PER_SEQ */
+    int32_t reserved;
+    const int32_t *seq_cap;   /* host [B]: token capacity of each sequence's extent (copied);
+                                 all equal in KV_TOKEN_MAJOR */
+    uint64_t lba_start;       /* start LBA of the first direct-path tensor */
+    uint64_t region_blocks;   /* sectors the LBA region holds, counted from LBA 0, or KV_UNBOUNDED */
+    uint64_t pc_budget_bytes; /* X: bytes admitted to the page-cache path */
+    uint64_t pageable_bytes;  /* bytes the pageable arena holds, or KV_UNBOUNDED */
+} kv_plan_desc_t;
+
+typedef struct kv_plan_info {
+    int32_t n_layers, n_kv_heads, n_q_heads, head_dim, batch, dtype, sector_bytes, chunk_tokens, extent_mode;
+    int32_t n_pagecache_layers;   /* n_1 of Alg. 1: layers [0, n_1) take the page-cache path */
+    uint64_t row_bytes;           /* one token row of an extent: B*H*D*2 (token-major) or H*D*2 */
+    uint64_t tensor_blocks;       /* n_blocks of every tensor (padded) */
+    uint64_t tensor_payload_bytes;
+    uint64_t region_bytes_needed;   /* (lba_start + sum of direct n_blocks) * sector_bytes */
+    uint64_t pageable_bytes_needed; /* sum of page-cache-path n_blocks * sector_bytes */
+} kv_plan_info_t;
+
+/* One entry of the map M (Eq. 3-4) plus the page-cache-path twin. */
+typedef struct kv_extent {
+    int32_t path;       /* KV_PATH_* */
+    int32_t reserved;
+    uint64_t lba_start; /* direct path; 0 on the page-cache path */
+    uint64_t n_blocks;
+    uint64_t file_off;  /* byte offset in the pageable arena; 0 on the direct path */
+    uint64_t bytes;     /* unpadded payload */
+} kv_extent_t;
+
+/* One per-chunk command (Eq. 9-11). */
+typedef struct kv_cmd {
+    uint64_t slba;    /* start LBA (direct) or sector index in the arena (page-cache path) */
+    uint64_t buf_off; /* dbuf - buf_ptr: byte offset in the request's host/staging image */
+    uint32_t nlb;     /* 0-based block count: nlb + 1 sectors move */
+    uint32_t tok0;    /* first token row of the chunk */
+    uint32_t ntok;    /* token rows in the chunk */
+    uint32_t reserved;
+} kv_cmd_t;
+
+/* Attention-side KV buffers.  All arrays named "host" are read during the call only. */
+typedef struct kv_view {
+    int32_t layout;   /* KV_LAYOUT_* */
+    int32_t n_layers; /* entries in k_layers / v_layers */
+    void *const *k_layers; /* host array of device pointers, 16-byte aligned */
+    void *const *v_layers; /* host array of device pointers, 16-byte aligned */
+    uint64_t layer_bytes;  /* bytes addressable behind every k/v pointer (bounds check) */
+    /* KV_LAYOUT_BHSD: strides in elements (multiples of 8); S_alloc rows exist per (b,h) */
+    int64_t stride_b, stride_h, stride_s;
+    int32_t s_alloc;
+    /* KV_LAYOUT_PAGED */
+    int32_t block_tokens;       /* tokens per block (16) */
+    int32_t n_pool_blocks;      /* blocks in every pool */
+    int32_t max_blocks_per_seq; /* row length of block_table */
+    const int32_t *block_table; /* device [B, max_blocks_per_seq]; ids outside [0,n_pool) are skipped */
+    /* valid tokens per sequence */
+    const int32_t *seq_lens_host; /* host [B] */
+    const int32_t *seq_lens_dev;  /* device [B] (decode attention reads it) */
+} kv_view_t;
+
+typedef struct kv_attn_args {
+    const void *const *q_layers; /* host array [n_layers] of device pointers, each [B, H_q, D] 16-bit */
+    void *const *out_layers;     /* host array [n_layers] of device pointers, each [B, H_q, D] */
+    int32_t out_dtype;           /* KV_OUT_* */
+    int32_t n_splits;            /* 0 = choose */
+} kv_attn_args_t;
+
+#define KV_KERNEL_PACK 0
+#define KV_KERNEL_UNPACK 1
+#define KV_KERNEL_ATTN_PARTIAL 2
+#define KV_KERNEL_ATTN_COMBINE 3
+
+#define KV_PIPE_TIME_KERNELS 1u /* bracket every kernel with hipEvents and fill kernel_ms */
+
+typedef struct kv_pipe_opts {
+    int32_t span_chunks;  /* chunks per kernel launch and staging slot; 0 = a whole tensor */
+    int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
+    uint32_t flags;       /* KV_PIPE_* */
+    int32_t reserved;
+} kv_pipe_opts_t;
+
+typedef struct kv_pipe_stats {
+    double wall_s;            /* call entry to drain */
+    uint64_t bytes_direct;    /* bytes moved over the host link for direct-path tensors (with pad) */
+    uint64_t bytes_pagecache; /* same for page-cache-path tensors */
+    uint32_t n_chunks;        /* chunk commands issued */
+    uint32_t n_spans;         /* staging slots filled */
+    uint32_t max_in_flight;   /* largest number of chunk commands outstanding at once */
+    uint32_t kernel_launches[4];
+    float kernel_ms[4];       /* summed event-bracketed time per kernel kind (KV_PIPE_TIME_KERNELS) */
+} kv_pipe_stats_t;
+
+/* ------------------------------------------------------------------------------------------ */
+/* Planner (host only, integer arithmetic; usable without a GPU)                              */
+/* ------------------------------------------------------------------------------------------ */
+
+/*
+ * kv_layout_plan -- Alg. 1 (KPU residency planner) followed by the LBA bind of Eq. 3-6.
+ *   n_1 = min(floor(X / (2*S_kpu)), L) with S_kpu = tensor_blocks*sector_bytes; layers [0,n_1) go to
+ *   the page-cache path, the rest to the direct path.  Direct tensors get lba_start by the recurrence
+ *   lba_start(n+1) = lba_start(n) + n_blocks(n) from desc->lba_start; n_blocks = ceil(bytes / sector)
+ *   (zero padding; equal to Eq. 5 under the paper's alignment precondition).  Page-cache-path tensors
+ *   get file_off by the same padded recurrence from 0.
+ * desc: host.  *out: new plan, owned by the library, freed by kv_plan_destroy.
+ * Errors: KV_EINVAL (shape/dtype/sector/mode, non-uniform caps in token-major), KV_EALIGN
+ * (chunk_tokens*row_bytes not a sector multiple), KV_ENOSPC (region_blocks or pageable_bytes too small).
+ */
+int kv_layout_plan(const kv_plan_desc_t *desc, kv_plan_t **out);
+void kv_plan_destroy(kv_plan_t *plan);
+
+int kv_plan_info(const kv_plan_t *plan, kv_plan_info_t *out);
+/* Map entry of tensor (layer, kind) -- Eq. 3-4.  KV_ERANGE for a bad layer, KV_EINVAL for a bad kind. */
+int kv_plan_tensor(const kv_plan_t *plan, int layer, int kind, kv_extent_t *out);
+/* Blocks before sequence seq's sub-extent inside a tensor's extent (0 in token-major mode). */
+int kv_plan_seq_base(const kv_plan_t *plan, int seq, uint64_t *base_blocks);
+
+/*
+ * kv_plan_translate -- Alg. 2 for whole token rows: offset indices (tok0, 0, 0) in the target shape
+ * (S_cap, B*H, D) [token-major; seq must be 0 or KV_SEQ_ALL] or (cap_seq, H, D) [per-sequence],
+ * source shape (ntok, ., D).  *slba = first sector (LBA on the direct path, sector index in the
+ * arena on the page-cache path); *req_bytes = ntok*row_bytes, rounded up to a sector multiple when
+ * the range ends at the extent tail.
+ * Errors: KV_EALIGN if tok0*row_bytes is not a sector multiple, or the range ends inside a sector
+ * short of the tail; KV_ERANGE if tok0+ntok exceeds the capacity; KV_EINVAL for ntok <= 0, tok0 < 0.
+ */
+int kv_plan_translate(const kv_plan_t *plan, int layer, int kind, int seq, int tok0, int ntok,
+                      uint64_t *slba, uint64_t *req_bytes);
+
+/*
+ * kv_plan_chunk_cmds -- Eq. 7-11 over the whole extent of (layer, kind) [token-major] or the whole
+ * sub-extent of sequence seq [per-sequence], with chunk_bytes = chunk_tokens*row_bytes
+ * (chunk_tokens = 0 takes the plan's).  Writes min(*n, cap) commands to out (host, caller-owned;
+ * may be NULL with cap = 0 to query the count) and the total count to *n.  buf_off counts from the
+ * first byte of that (sub-)extent.
+ */
+int kv_plan_chunk_cmds(const kv_plan_t *plan, int layer, int kind, int seq, int chunk_tokens,
+                       kv_cmd_t *out, int cap, int *n);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Kernels (asynchronous on the given stream)                                                 */
+/* ------------------------------------------------------------------------------------------ */
+
+/*
+ * kv_offload_pack -- attention-side layout -> extent byte order (row-major (S, B*H, D), Sec. IV-B
+ * precondition and Alg. 2's row-major offset), for tensor (layer, kind).
+ *   seq >= 0 (or 0 in token-major): token rows [tok0, tok0+ntok) of that (sub-)extent are written to
+ *     dst_dev[0 ..); the byte count is kv_plan_translate's req_bytes (zero pad up to the sector
+ *     boundary when the range reaches the tail), same error rules.
+ *   seq = KV_SEQ_ALL (tok0 = ntok = 0): the whole extent image, n_blocks*sector bytes: rows
+ *     [0, len_b) of every sequence (src->seq_lens_host, <= capacity; uniform in token-major) and
+ *     zeros up to each (sub-)extent's end.
+ * src: host struct, device buffers; dst_dev: device, 16-byte aligned, dst_bytes >= bytes written
+ * (else KV_ENOSPC).  Rows must exist in the source (BHSD: < s_alloc; paged: < seq_lens_host[b]) else
+ * KV_ERANGE.  Nothing is launched on error.
+ */
+int kv_offload_pack(const kv_plan_t *plan, int layer, int kind, const kv_view_t *src, int seq,
+                    int tok0, int ntok, void *dst_dev, size_t dst_bytes, void *hip_stream);
+
+/*
+ * kv_reload_unpack -- the inverse: bytes at src_dev[0 ..) in extent order -> the view's rows.  Only
+ * the addressed valid token rows are written; pad bytes are ignored; every other element of the
+ * view is left untouched.  Same arguments and errors as kv_offload_pack (src_bytes >= bytes read).
+ */
+int kv_reload_unpack(const kv_plan_t *plan, int layer, int kind, const void *src_dev, size_t src_bytes,
+                     const kv_view_t *dst, int seq, int tok0, int ntok, void *hip_stream);
+
+/*
+ * kv_decode_attn -- one decode-attention step of one layer over resident KV (Sec. II-A: similarity of
+ * the query with the keys weights the values): out[b,hq,:] = softmax_j(q[b,hq,:].K[b,h,j,:] / sqrt(D))
+ * V[b,h,j,:], j in [0, len_b), h = hq / (H_q/H); fp32 accumulation; split-K over tokens with a
+ * combine pass.  len_b = kv->seq_lens_dev (device) with kv->seq_lens_host as its host mirror; a
+ * sequence of length 0 yields zeros.
+ * q: device [B,H_q,D] 16-bit, 16-byte aligned; out: device [B,H_q,D] fp32 or 16-bit (out_dtype);
+ * workspace: device, >= kv_decode_attn_workspace() bytes (else KV_ENOSPC); n_splits 0 = choose.
+ */
+int kv_decode_attn(const kv_plan_t *plan, const kv_view_t *kv, int layer, const void *q, void *out,
+                   int out_dtype, int n_splits, void *workspace, size_t ws_bytes, void *hip_stream);
+/* Bytes of workspace kv_decode_attn needs for up to max_len tokens per sequence (n_splits 0 = chosen). */
+size_t kv_decode_attn_workspace(const kv_plan_t *plan, int n_splits, int max_len);
+
+/* ------------------------------------------------------------------------------------------ */
+/* Chunk pipeline (blocking; returns after the drain)                                         */
+/* ------------------------------------------------------------------------------------------ */
+
+/*
+ * kv_pipeline_run -- move layers [layer_begin, layer_end) between the view and the storage model,
+ * tensor by tensor (K then V), each as the per-chunk commands of Eq. 7-11, with at most `depth`
+ * commands outstanding: a new command is issued only after the oldest has completed when `depth`
+ * are in flight, and the call drains all of them before returning (Sec. IV-B "Data Flow").
+ * Direct-path tensors move HBM <-> lba_region + slba*sector in two hops' worth of DMA only (Co-DMA:
+ * the region is the buffer both sides address); page-cache-path tensors take the third hop, a host
+ * memcpy between a pinned bounce ring and pageable + file_off (Sec. IV-B, 3-hop vs 2-hop).
+ * KV_DIR_OFFLOAD: pack -> D2H.  KV_DIR_RELOAD: H2D -> unpack.  KV_DIR_RELOAD_ATTN: also decode
+ * attention per layer into attn->out_layers[layer].
+ * lba_region: pinned host memory (hipHostMalloc), region_bytes >= region_bytes_needed if any
+ * direct-path layer is in range; pageable: ordinary host memory, pageable_bytes >=
+ * pageable_bytes_needed if any page-cache-path layer is in range.  chunk_tokens 0 = the plan's.
+ * The library owns its streams, events, staging slots, bounce ring and worker threads (created on
+ * first use per plan, freed by kv_plan_destroy).  Calls on one plan must not overlap.
+ * stats: host, may be NULL.
+ */
+int kv_pipeline_run(kv_plan_t *plan, int dir, int layer_begin, int layer_end, const kv_view_t *view,
+                    void *lba_region, size_t region_bytes, void *pageable, size_t pageable_bytes,
+                    int chunk_tokens, int depth, const kv_attn_args_t *attn, const kv_pipe_opts_t *opts,
+                    kv_pipe_stats_t *stats);
+
+/* ------------------------------------------------------------------------------------------ */
+int kv_last_hip_error(void);       /* hipError_t of the last KV_EHIP on this thread, else 0 */
+const char *kv_strerror(int code); /* static string */
+int kv_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVBLADE_H */

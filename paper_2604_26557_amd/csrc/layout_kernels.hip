@@ -1,0 +1,310 @@
+// Pack / unpack: the byte permutation between the attention-side KV layout (strided [B,H,S,D] or a
+// paged block pool) and extent order, the row-major (S, B*H, D) array of Sec. IV-B.
+//
+// The innermost D row (D*2 bytes, a multiple of 16) is preserved by the permutation, so the kernels
+// move whole 16-byte vectors: one lane = one global_load_dwordx4 + one global_store_dwordx4.
+// Threads are laid out as (rx, ty): rx walks the vectors of one extent row (consecutive lanes ->
+// consecutive extent bytes, so a wavefront touches >= 1 KiB of contiguous extent and whole head rows
+// of the source), ty walks token rows.  The (b, h, d) decomposition of a row position is done once
+// per thread per row position and reused for every token, so the inner loop is adds, U independent
+// 16-byte loads, then U stores.  HBM-bound: 2 bytes of traffic per payload byte, no reuse, no LDS.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <climits>
+
+#include "plan.hpp"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kMaxSegs = 32;
+
+// Attention-side addressing, in 16-byte vectors.
+struct SrcDesc {
+    u32x4 *base;
+    long long sb, sh, ss;  // strided layout: vectors per batch / head / token step
+    const int *table;      // paged layout
+    int max_blocks, bt, bt_shift, n_pool;
+    int H, dvec;           // heads, vectors per head row
+};
+
+// One contiguous run of token rows of one (sub-)extent inside the image buffer.
+struct Seg {
+    unsigned long long img_off;  // vector index in the image of row 0 of this run
+    unsigned long long pad_off;  // vector index of the first pad vector (pack only)
+    unsigned int pad_vecs;       // zero vectors to write (pack only)
+    int b;                       // sequence, or -1: the batch index is part of the row position
+    int tok0, ntok;
+};
+
+struct SegTable {
+    Seg seg[kMaxSegs];
+};
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld(const u32x4 *p)
+{
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st(u32x4 *p, u32x4 v)
+{
+    if (NT) __builtin_nontemporal_store(v, p); else *p = v;
+}
+
+// PACK: source -> image.  !PACK: image -> source.  U = token rows in flight per thread.
+template <bool PACK, bool PAGED, int U>
+__global__ void __launch_bounds__(kThreads)
+kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, int rx_log2, int tpb)
+{
+    const Seg sg = segs.seg[blockIdx.y];
+    const int tid = threadIdx.x;
+
+    if (PACK && sg.pad_vecs) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (unsigned int i = blockIdx.x * kThreads + tid; i < sg.pad_vecs; i += gridDim.x * kThreads)
+            img[sg.pad_off + i] = z;
+    }
+
+    const int t_begin = blockIdx.x * tpb;
+    if (t_begin >= sg.ntok) return;
+    const int t_end = min(sg.ntok, t_begin + tpb);
+
+    const int RX = 1 << rx_log2;
+    const int TY = kThreads >> rx_log2;
+    const int rx = tid & (RX - 1);
+    const int ty = tid >> rx_log2;
+    const int hd = s.H * s.dvec;
+
+    for (int r = rx; r < rowv; r += RX) {
+        int b, rem;
+        if (sg.b >= 0) { b = sg.b; rem = r; } else { b = r / hd; rem = r - b * hd; }
+        const int h = rem / s.dvec;
+        const int dv = rem - h * s.dvec;
+        const long long row_off = PAGED ? 0 : (long long)b * s.sb + (long long)h * s.sh + dv;
+        const int *tbl = PAGED ? s.table + (long long)b * s.max_blocks : nullptr;
+
+        for (int t0 = t_begin + ty; t0 < t_end; t0 += TY * U) {
+            u32x4 v[U];
+            long long a[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + u * TY;
+                ok[u] = t < t_end;
+                a[u] = 0;
+                if (ok[u]) {
+                    const int tok = sg.tok0 + t;
+                    if (PAGED) {
+                        const int j = s.bt_shift >= 0 ? (tok >> s.bt_shift) : (tok / s.bt);
+                        const int slot = tok - j * s.bt;
+                        const int blk = tbl[j];
+                        ok[u] = (unsigned)blk < (unsigned)s.n_pool;  // ids outside the pool are skipped
+                        a[u] = (((long long)blk * s.H + h) * s.bt + slot) * s.dvec + dv;
+                    } else {
+                        a[u] = row_off + (long long)tok * s.ss;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const unsigned long long i = sg.img_off + (unsigned long long)(t0 + u * TY) * rowv + r;
+                if (ok[u]) v[u] = PACK ? ld<true>(s.base + a[u]) : ld<true>(img + i);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const unsigned long long i = sg.img_off + (unsigned long long)(t0 + u * TY) * rowv + r;
+                if (PACK) {
+                    // a skipped block id still owns its bytes of the image: they read as zero
+                    const bool in = (t0 + u * TY) < t_end;
+                    const u32x4 z = {0u, 0u, 0u, 0u};
+                    if (in) st<true>(img + i, ok[u] ? v[u] : z);
+                } else if (ok[u]) {
+                    st<true>(s.base + a[u], v[u]);
+                }
+            }
+        }
+    }
+}
+
+int check_view(const kv_plan *p, const kv_view_t *v, int layer)
+{
+    if (!v || !v->k_layers || !v->v_layers || !v->seq_lens_host) return KV_EINVAL;
+    if (layer < 0 || layer >= p->L || layer >= v->n_layers) return KV_ERANGE;
+    if (!v->k_layers[layer] || !v->v_layers[layer]) return KV_EINVAL;
+    if (((uintptr_t)v->k_layers[layer] | (uintptr_t)v->v_layers[layer]) & 15) return KV_EINVAL;
+    if (v->layout == KV_LAYOUT_BHSD) {
+        if (v->stride_b < 0 || v->stride_h < 0 || v->stride_s < 0 || v->s_alloc < 0) return KV_EINVAL;
+        if ((v->stride_b | v->stride_h | v->stride_s) & 7) return KV_EINVAL;
+        if (v->stride_s < p->D) return KV_EINVAL;
+    } else if (v->layout == KV_LAYOUT_PAGED) {
+        if (!v->block_table || v->block_tokens < 1 || v->n_pool_blocks < 0 || v->max_blocks_per_seq < 0)
+            return KV_EINVAL;
+        const uint64_t pool = (uint64_t)v->n_pool_blocks * p->H * v->block_tokens * p->D * 2;
+        if (pool > v->layer_bytes) return KV_ERANGE;
+    } else {
+        return KV_EINVAL;
+    }
+    return KV_OK;
+}
+
+// Rows [tok0, tok0+ntok) of sequence b (or of every sequence when b < 0) must exist in the view.
+int check_rows(const kv_plan *p, const kv_view_t *v, int b, int tok0, int ntok)
+{
+    const int b0 = b < 0 ? 0 : b, b1 = b < 0 ? p->B : b + 1;
+    const long long last = (long long)tok0 + ntok;  // one past the last row
+    if (ntok == 0) return KV_OK;
+    if (v->layout == KV_LAYOUT_BHSD) {
+        if (last > v->s_alloc) return KV_ERANGE;
+        const uint64_t max_elem = (uint64_t)(b1 - 1) * v->stride_b + (uint64_t)(p->H - 1) * v->stride_h +
+                                  (uint64_t)(last - 1) * v->stride_s + p->D;
+        if (max_elem * 2 > v->layer_bytes) return KV_ERANGE;
+    } else {
+        for (int i = b0; i < b1; ++i) {
+            if (last > v->seq_lens_host[i]) return KV_ERANGE;
+            if (kvb::ceil_div((uint64_t)last, (uint64_t)v->block_tokens) > (uint64_t)v->max_blocks_per_seq)
+                return KV_ERANGE;
+        }
+    }
+    return KV_OK;
+}
+
+SrcDesc make_src(const kv_plan *p, const kv_view_t *v, int layer, int kind)
+{
+    SrcDesc s{};
+    s.base = (u32x4 *)(kind == KV_K ? v->k_layers[layer] : v->v_layers[layer]);
+    s.H = p->H;
+    s.dvec = p->D / 8;
+    if (v->layout == KV_LAYOUT_BHSD) {
+        s.sb = v->stride_b / 8; s.sh = v->stride_h / 8; s.ss = v->stride_s / 8;
+    } else {
+        s.table = v->block_table;
+        s.max_blocks = v->max_blocks_per_seq;
+        s.bt = v->block_tokens;
+        s.bt_shift = (s.bt & (s.bt - 1)) == 0 ? __builtin_ctz((unsigned)s.bt) : -1;
+        s.n_pool = v->n_pool_blocks;
+    }
+    return s;
+}
+
+int g_tile_bytes = 64 * 1024;  // extent bytes one workgroup moves
+
+template <bool PACK>
+int launch(const kv_plan *p, const kv_view_t *v, int layer, int kind, const Seg *segs, int nseg, void *img,
+           hipStream_t stream)
+{
+    const int rowv = (int)(p->row_bytes / 16);
+    int rx_log2 = 0;
+    while ((1 << rx_log2) < rowv && rx_log2 < 8) ++rx_log2;
+    const int TY = kThreads >> rx_log2;
+    constexpr int U = 4;
+    int tpb = (int)std::max<long long>(1, g_tile_bytes / (long long)p->row_bytes);
+    tpb = (tpb + TY * U - 1) / (TY * U) * (TY * U);
+    const SrcDesc s = make_src(p, v, layer, kind);
+    const bool paged = v->layout == KV_LAYOUT_PAGED;
+
+    for (int g0 = 0; g0 < nseg; g0 += kMaxSegs) {
+        const int n = std::min(kMaxSegs, nseg - g0);
+        SegTable tab{};
+        int max_tok = 0;
+        for (int i = 0; i < n; ++i) {
+            tab.seg[i] = segs[g0 + i];
+            max_tok = std::max(max_tok, segs[g0 + i].ntok);
+        }
+        dim3 grid((unsigned)std::max(1, (max_tok + tpb - 1) / tpb), (unsigned)n);
+        if (paged)
+            hipLaunchKernelGGL((kv_layout_kernel<PACK, true, U>), grid, dim3(kThreads), 0, stream, s, (u32x4 *)img,
+                               tab, rowv, rx_log2, tpb);
+        else
+            hipLaunchKernelGGL((kv_layout_kernel<PACK, false, U>), grid, dim3(kThreads), 0, stream, s, (u32x4 *)img,
+                               tab, rowv, rx_log2, tpb);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
+    }
+    return KV_OK;
+}
+
+template <bool PACK>
+int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int tok0, int ntok, void *img,
+        size_t img_bytes, void *hip_stream)
+{
+    if (!p || !img) return KV_EINVAL;
+    if (kind != KV_K && kind != KV_V) return KV_EINVAL;
+    if ((uintptr_t)img & 15) return KV_EINVAL;
+    int rc = check_view(p, v, layer);
+    if (rc != KV_OK) return rc;
+    if (p->row_bytes / 16 > (uint64_t)INT_MAX) return KV_EINVAL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const uint64_t sec = (uint64_t)p->sector;
+
+    std::vector<Seg> segs;
+    if (seq == KV_SEQ_ALL && tok0 == 0 && ntok == 0) {
+        // Whole extent image.
+        if (img_bytes < p->tensor_blocks * sec) return KV_ENOSPC;
+        if (p->mode == KV_TOKEN_MAJOR) {
+            const int len = v->seq_lens_host[0];
+            for (int b = 0; b < p->B; ++b)
+                if (v->seq_lens_host[b] != len) return KV_EINVAL;
+            if (len < 0 || len > p->cap[0]) return KV_ERANGE;
+            rc = check_rows(p, v, -1, 0, len);
+            if (rc != KV_OK) return rc;
+            Seg s{};
+            s.img_off = 0; s.b = -1; s.tok0 = 0; s.ntok = len;
+            s.pad_off = (uint64_t)len * p->row_bytes / 16;
+            s.pad_vecs = (unsigned)((p->tensor_blocks * sec - (uint64_t)len * p->row_bytes) / 16);
+            segs.push_back(s);
+        } else {
+            for (int b = 0; b < p->B; ++b) {
+                const int len = v->seq_lens_host[b];
+                if (len < 0 || len > p->cap[b]) return KV_ERANGE;
+                rc = check_rows(p, v, b, 0, len);
+                if (rc != KV_OK) return rc;
+                const uint64_t sub_bytes = kvb::round_up((uint64_t)p->cap[b] * p->row_bytes, sec);
+                Seg s{};
+                s.img_off = p->seq_base[b] * sec / 16;
+                s.b = b; s.tok0 = 0; s.ntok = len;
+                s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
+                s.pad_vecs = (unsigned)((sub_bytes - (uint64_t)len * p->row_bytes) / 16);
+                if (len > 0 || s.pad_vecs > 0) segs.push_back(s);
+            }
+        }
+    } else {
+        kvb::RowRange r;
+        rc = kvb::resolve_rows(p, seq, tok0, ntok, &r);
+        if (rc != KV_OK) return rc;
+        if (img_bytes < (PACK ? r.req_bytes : r.payload)) return KV_ENOSPC;
+        const int b = p->mode == KV_TOKEN_MAJOR ? -1 : r.b;
+        rc = check_rows(p, v, b, tok0, ntok);
+        if (rc != KV_OK) return rc;
+        Seg s{};
+        s.img_off = 0; s.b = b; s.tok0 = tok0; s.ntok = ntok;
+        s.pad_off = r.payload / 16;
+        s.pad_vecs = (unsigned)((r.req_bytes - r.payload) / 16);
+        segs.push_back(s);
+    }
+    if (!PACK)
+        for (Seg &s : segs) s.pad_vecs = 0;
+    if (segs.empty()) return KV_OK;
+    return launch<PACK>(p, v, layer, kind, segs.data(), (int)segs.size(), img, stream);
+}
+
+}  // namespace
+
+namespace kvb {
+void set_layout_tile_bytes(int bytes) { if (bytes >= 1024) g_tile_bytes = bytes; }
+}
+
+extern "C" int kv_offload_pack(const kv_plan_t *plan, int layer, int kind, const kv_view_t *src, int seq, int tok0,
+                               int ntok, void *dst_dev, size_t dst_bytes, void *hip_stream)
+{
+    return run<true>(plan, layer, kind, src, seq, tok0, ntok, dst_dev, dst_bytes, hip_stream);
+}
+
+extern "C" int kv_reload_unpack(const kv_plan_t *plan, int layer, int kind, const void *src_dev, size_t src_bytes,
+                                const kv_view_t *dst, int seq, int tok0, int ntok, void *hip_stream)
+{
+    return run<false>(plan, layer, kind, dst, seq, tok0, ntok, const_cast<void *>(src_dev), src_bytes, hip_stream);
+}

@@ -1,0 +1,514 @@
+// Chunk pipeline: moves KV tensors between HBM and the storage model as the per-chunk commands of
+// Eq. 7-11, overlapping the GPU marshalling kernels with host-link DMA and, on the page-cache path,
+// with the host memcpy hop (Sec. IV-B "Co-DMA" / "Data Flow"; 3-hop vs 2-hop paths).
+//
+// Two granularities are kept apart on purpose:
+//  * DMA runs per chunk command; at most `depth` commands are outstanding (the queue-depth rule:
+//    when `depth` are in flight the oldest is harvested before the next is issued; a final drain
+//    collects the rest).  hipEvents play the role of completion-queue entries.
+//  * Kernels run per span = a whole tensor by default (HBM is large, so staging a whole extent costs
+//    nothing and the pack / unpack launches are big enough to run at HBM speed), or every
+//    `span_chunks` chunks on request.
+// Streams: one for kernels, one for copies; events order pack -> D2H and H2D -> unpack -> attention
+// and guard staging-slot reuse.  All streams keep the default priority.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "plan.hpp"
+
+namespace {
+
+#define KV_HIP(call)                                       \
+    do {                                                   \
+        hipError_t e_ = (call);                            \
+        if (e_ != hipSuccess) {                            \
+            kvb::set_hip_error((int)e_);                   \
+            return KV_EHIP;                                \
+        }                                                  \
+    } while (0)
+
+// Inside the issue loops: record the error and leave the loop so that the drain still runs.
+#define KV_HIP_BRK(call)                                   \
+    {                                                      \
+        hipError_t e_ = (call);                            \
+        if (e_ != hipSuccess) {                            \
+            kvb::set_hip_error((int)e_);                   \
+            err = KV_EHIP;                                 \
+            break;                                         \
+        }                                                  \
+    }
+
+struct CopyTask {
+    void *dst;
+    const void *src;
+    size_t bytes;
+    hipEvent_t wait_ev;  // DMA that must land first (offload), or nullptr
+    std::atomic<int> *pending;
+};
+
+// Host threads of the page-cache path's memcpy hop.
+class Workers {
+public:
+    void start(int n, int device)
+    {
+        if ((int)threads_.size() == n) return;
+        stop();
+        quit_ = false;
+        for (int i = 0; i < n; ++i) threads_.emplace_back([this, device] { loop(device); });
+    }
+    void stop()
+    {
+        {
+            std::lock_guard<std::mutex> g(mu_);
+            quit_ = true;
+        }
+        cv_.notify_all();
+        for (auto &t : threads_) t.join();
+        threads_.clear();
+    }
+    void push(const CopyTask &t)
+    {
+        {
+            std::lock_guard<std::mutex> g(mu_);
+            q_.push_back(t);
+        }
+        cv_.notify_one();
+    }
+    int size() const { return (int)threads_.size(); }
+    ~Workers() { stop(); }
+
+private:
+    void loop(int device)
+    {
+        (void)hipSetDevice(device);
+        for (;;) {
+            CopyTask t;
+            {
+                std::unique_lock<std::mutex> g(mu_);
+                cv_.wait(g, [this] { return quit_ || !q_.empty(); });
+                if (q_.empty()) return;
+                t = q_.front();
+                q_.pop_front();
+            }
+            if (t.wait_ev) (void)hipEventSynchronize(t.wait_ev);
+            std::memcpy(t.dst, t.src, t.bytes);
+            t.pending->fetch_sub(1, std::memory_order_release);
+        }
+    }
+    std::vector<std::thread> threads_;
+    std::deque<CopyTask> q_;
+    std::mutex mu_;
+    std::condition_variable cv_;
+    bool quit_ = false;
+};
+
+struct Chunk {
+    uint64_t host_off;   // byte offset in the LBA region (slba * sector) or in the arena
+    uint64_t stage_off;  // byte offset inside the span's staging slot
+    uint64_t bytes;      // (nlb + 1) * sector
+    int span;
+    bool first, last;    // first / last chunk of its span
+};
+
+struct Span {
+    int layer, kind, seq, tok0, ntok;  // seq = KV_SEQ_ALL: whole tensor
+    uint64_t bytes;                    // image bytes
+    int path;
+    bool last_of_layer;
+};
+
+struct Entry {
+    hipEvent_t ev = nullptr;
+    std::atomic<int> pending{0};
+};
+
+}  // namespace
+
+struct kv_pipeline {
+    int device = 0;
+    hipStream_t s_compute = nullptr, s_copy = nullptr;
+    void *staging = nullptr;
+    size_t staging_bytes = 0;
+    void *bounce = nullptr;
+    size_t bounce_bytes = 0;
+    void *attn_ws = nullptr;
+    size_t attn_ws_bytes = 0;
+    std::vector<hipEvent_t> ev_ready, ev_free;  // per staging slot
+    std::vector<Entry> ring;                    // per in-flight command
+    std::vector<hipEvent_t> timing;             // pairs
+    Workers workers;
+
+    ~kv_pipeline()
+    {
+        workers.stop();
+        (void)hipSetDevice(device);
+        if (s_copy) (void)hipStreamSynchronize(s_copy);
+        if (s_compute) (void)hipStreamSynchronize(s_compute);
+        for (auto e : ev_ready) (void)hipEventDestroy(e);
+        for (auto e : ev_free) (void)hipEventDestroy(e);
+        for (auto &e : ring) if (e.ev) (void)hipEventDestroy(e.ev);
+        for (auto e : timing) (void)hipEventDestroy(e);
+        if (staging) (void)hipFree(staging);
+        if (bounce) (void)hipHostFree(bounce);
+        if (attn_ws) (void)hipFree(attn_ws);
+        if (s_copy) (void)hipStreamDestroy(s_copy);
+        if (s_compute) (void)hipStreamDestroy(s_compute);
+    }
+};
+
+namespace {
+
+int ensure_events(std::vector<hipEvent_t> &v, size_t n, unsigned flags)
+{
+    while (v.size() < n) {
+        hipEvent_t e;
+        KV_HIP(hipEventCreateWithFlags(&e, flags));
+        v.push_back(e);
+    }
+    return KV_OK;
+}
+
+int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, size_t chunk_bytes_max, bool need_bounce,
+                    int n_workers, size_t attn_ws_bytes, size_t n_timing)
+{
+    if (!p->pipe) {
+        p->pipe = new kv_pipeline();
+        KV_HIP(hipGetDevice(&p->pipe->device));
+        KV_HIP(hipStreamCreateWithFlags(&p->pipe->s_compute, hipStreamNonBlocking));
+        KV_HIP(hipStreamCreateWithFlags(&p->pipe->s_copy, hipStreamNonBlocking));
+    }
+    kv_pipeline *q = p->pipe;
+    const size_t need = n_slots * slot_bytes;
+    if (q->staging_bytes < need) {
+        if (q->staging) KV_HIP(hipFree(q->staging));
+        q->staging = nullptr; q->staging_bytes = 0;
+        KV_HIP(hipMalloc(&q->staging, need));
+        q->staging_bytes = need;
+    }
+    if (need_bounce && q->bounce_bytes < (size_t)depth * chunk_bytes_max) {
+        if (q->bounce) KV_HIP(hipHostFree(q->bounce));
+        q->bounce = nullptr; q->bounce_bytes = 0;
+        KV_HIP(hipHostMalloc(&q->bounce, (size_t)depth * chunk_bytes_max, hipHostMallocDefault));
+        q->bounce_bytes = (size_t)depth * chunk_bytes_max;
+    }
+    if (attn_ws_bytes && q->attn_ws_bytes < attn_ws_bytes) {
+        if (q->attn_ws) KV_HIP(hipFree(q->attn_ws));
+        q->attn_ws = nullptr; q->attn_ws_bytes = 0;
+        KV_HIP(hipMalloc(&q->attn_ws, attn_ws_bytes));
+        q->attn_ws_bytes = attn_ws_bytes;
+    }
+    int rc = ensure_events(q->ev_ready, n_slots, hipEventDisableTiming);
+    if (rc) return rc;
+    rc = ensure_events(q->ev_free, n_slots, hipEventDisableTiming);
+    if (rc) return rc;
+    if (q->ring.size() < (size_t)depth) {
+        std::vector<Entry> bigger((size_t)depth);
+        for (size_t i = 0; i < q->ring.size(); ++i) bigger[i].ev = q->ring[i].ev;
+        q->ring.swap(bigger);
+    }
+    for (auto &e : q->ring)
+        if (!e.ev) KV_HIP(hipEventCreateWithFlags(&e.ev, hipEventDisableTiming));
+    rc = ensure_events(q->timing, n_timing, hipEventDefault);
+    if (rc) return rc;
+    if (need_bounce) q->workers.start(n_workers, q->device);
+    return KV_OK;
+}
+
+inline void spin_until_zero(std::atomic<int> &a)
+{
+    int spins = 0;
+    while (a.load(std::memory_order_acquire) != 0) {
+        if (++spins > 2000) std::this_thread::yield();
+    }
+}
+
+}  // namespace
+
+extern "C" void kv_plan_destroy(kv_plan_t *plan)
+{
+    if (!plan) return;
+    delete plan->pipe;
+    delete plan;
+}
+
+extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer_end, const kv_view_t *view,
+                               void *lba_region, size_t region_bytes, void *pageable, size_t pageable_bytes,
+                               int chunk_tokens, int depth, const kv_attn_args_t *attn, const kv_pipe_opts_t *opts,
+                               kv_pipe_stats_t *stats)
+{
+    const auto t_start = std::chrono::steady_clock::now();
+    if (!p || !view) return KV_EINVAL;
+    if (dir != KV_DIR_OFFLOAD && dir != KV_DIR_RELOAD && dir != KV_DIR_RELOAD_ATTN) return KV_EINVAL;
+    if (layer_begin < 0 || layer_end > p->L || layer_begin > layer_end) return KV_ERANGE;
+    if (layer_end > view->n_layers) return KV_ERANGE;
+    if (depth < 1 || depth > 1024 || chunk_tokens < 0) return KV_EINVAL;
+    if (dir == KV_DIR_RELOAD_ATTN && (!attn || !attn->q_layers || !attn->out_layers)) return KV_EINVAL;
+    if (!view->seq_lens_host) return KV_EINVAL;
+    const int span_chunks = opts ? opts->span_chunks : 0;
+    const int n_workers = opts && opts->host_workers > 0 ? opts->host_workers : 8;
+    const bool time_kernels = opts && (opts->flags & KV_PIPE_TIME_KERNELS);
+    if (span_chunks < 0 || n_workers > 64) return KV_EINVAL;
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    if (layer_begin == layer_end) return KV_OK;
+
+    const uint64_t sec = (uint64_t)p->sector;
+    const uint64_t C = chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens;
+    const uint64_t chunk_bytes = C * p->row_bytes;
+    if (chunk_bytes % sec != 0) return KV_EALIGN;
+
+    // Which host buffers does this layer range need?
+    bool any_direct = false, any_pc = false;
+    for (int l = layer_begin; l < layer_end; ++l) (l < p->n1 ? any_pc : any_direct) = true;
+    if (any_direct) {
+        if (!lba_region) return KV_EINVAL;
+        if (region_bytes < p->region_bytes_needed) return KV_ENOSPC;
+        hipPointerAttribute_t at;
+        hipError_t e = hipPointerGetAttributes(&at, lba_region);
+        if (e != hipSuccess) { (void)hipGetLastError(); return KV_EINVAL; }  // not pinned
+        if (at.type != hipMemoryTypeHost) return KV_EINVAL;
+    }
+    if (any_pc) {
+        if (!pageable) return KV_EINVAL;
+        if (pageable_bytes < p->pageable_bytes_needed) return KV_ENOSPC;
+    }
+
+    // Valid lengths: a tensor moves rows [0, len_b) (padded to its extent); in span mode whole
+    // capacity rows are addressed, so lengths must equal capacities there.
+    for (int b = 0; b < p->B; ++b) {
+        const int len = view->seq_lens_host[b];
+        if (len < 0 || len > p->cap[b]) return KV_ERANGE;
+        if (span_chunks > 0 && len != p->cap[b]) return KV_EINVAL;
+    }
+
+    // ---- build the span and chunk lists -------------------------------------------------------
+    std::vector<Span> spans;
+    std::vector<Chunk> chunks;
+    std::vector<kv_cmd_t> cmds;
+    uint64_t slot_bytes = 0;
+    for (int l = layer_begin; l < layer_end; ++l) {
+        for (int kind = 0; kind < 2; ++kind) {
+            const kv_extent_t &ext = p->ext[2 * l + kind];
+            const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
+            if (span_chunks == 0) {
+                Span s{l, kind, KV_SEQ_ALL, 0, 0, p->tensor_blocks * sec, ext.path, false};
+                spans.push_back(s);
+            }
+            for (int b = 0; b < nseq; ++b) {
+                int rc = kvb::chunk_cmds(p, l, kind, b, (int)C, &cmds);
+                if (rc != KV_OK) return rc;
+                for (size_t i = 0; i < cmds.size(); ++i) {
+                    const kv_cmd_t &c = cmds[i];
+                    if (span_chunks > 0 && i % (size_t)span_chunks == 0) {
+                        const size_t j = std::min(cmds.size(), i + (size_t)span_chunks) - 1;
+                        Span s{l, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false};
+                        for (size_t k = i; k <= j; ++k) s.bytes += ((uint64_t)cmds[k].nlb + 1) * sec;
+                        spans.push_back(s);
+                    }
+                    Chunk ch;
+                    ch.host_off = c.slba * sec;
+                    ch.bytes = ((uint64_t)c.nlb + 1) * sec;
+                    ch.span = (int)spans.size() - 1;
+                    ch.stage_off = span_chunks == 0 ? p->seq_base[b] * sec + c.buf_off
+                                                    : c.buf_off - (uint64_t)spans.back().tok0 * p->row_bytes;
+                    ch.first = ch.last = false;
+                    const uint64_t host_cap = ext.path == KV_PATH_DIRECT ? region_bytes : pageable_bytes;
+                    if (ch.host_off + ch.bytes > host_cap) return KV_ENOSPC;
+                    chunks.push_back(ch);
+                }
+            }
+        }
+        if (!spans.empty()) spans.back().last_of_layer = true;
+    }
+    for (size_t i = 0; i < chunks.size(); ++i) {
+        chunks[i].first = i == 0 || chunks[i - 1].span != chunks[i].span;
+        chunks[i].last = i + 1 == chunks.size() || chunks[i + 1].span != chunks[i].span;
+    }
+    for (const Span &s : spans) slot_bytes = std::max(slot_bytes, s.bytes);
+    slot_bytes = kvb::round_up(slot_bytes, 4096);
+    const size_t n_slots = span_chunks == 0 ? 4 : std::max<size_t>(4, (size_t)depth);
+
+    size_t ws_bytes = 0;
+    if (dir == KV_DIR_RELOAD_ATTN) {
+        int max_len = 0;
+        for (int b = 0; b < p->B; ++b) max_len = std::max(max_len, view->seq_lens_host[b]);
+        ws_bytes = kv_decode_attn_workspace(p, attn->n_splits, max_len);
+    }
+    const size_t n_timing = time_kernels ? 2 * (spans.size() + 2 * (size_t)(layer_end - layer_begin)) : 0;
+    int rc = ensure_pipeline(p, n_slots, slot_bytes, depth, chunk_bytes, any_pc, n_workers, ws_bytes, n_timing);
+    if (rc != KV_OK) return rc;
+    kv_pipeline *q = p->pipe;
+    char *staging = (char *)q->staging;
+    const int pieces_max = std::max(1, q->workers.size());
+
+    // kernel timing bookkeeping
+    std::vector<int> timing_kind;
+    auto time_begin = [&](int kind) {
+        if (!time_kernels) return;
+        (void)hipEventRecord(q->timing[2 * timing_kind.size()], q->s_compute);
+        timing_kind.push_back(kind);
+    };
+    auto time_end = [&]() {
+        if (!time_kernels) return;
+        (void)hipEventRecord(q->timing[2 * (timing_kind.size() - 1) + 1], q->s_compute);
+    };
+
+    const bool offload = dir == KV_DIR_OFFLOAD;
+    const size_t N = chunks.size();
+    size_t n_waited = 0;  // chunks [0, n_waited) are known complete
+    uint32_t max_in_flight = 0;
+    int err = KV_OK;
+
+    // Chunk c owns ring entry c % depth from its start until it is known complete.
+    auto wait_complete = [&](size_t c) -> int {
+        Entry &e = q->ring[c % (size_t)depth];
+        KV_HIP(hipEventSynchronize(e.ev));
+        spin_until_zero(e.pending);
+        return KV_OK;
+    };
+    auto acquire = [&](size_t c) -> int {  // make ring entry of chunk c free
+        while (c >= n_waited + (size_t)depth) {
+            int r = wait_complete(n_waited);
+            if (r != KV_OK) return r;
+            ++n_waited;
+        }
+        return KV_OK;
+    };
+    auto host_ptr = [&](const Chunk &ch) -> char * {
+        return (spans[ch.span].path == KV_PATH_DIRECT ? (char *)lba_region : (char *)pageable) + ch.host_off;
+    };
+    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % (size_t)depth) * chunk_bytes; };
+    auto fan_out = [&](size_t c, void *dst, const void *src, size_t bytes, hipEvent_t ev) {
+        Entry &e = q->ring[c % (size_t)depth];
+        int pieces = (int)std::min<size_t>((size_t)pieces_max, std::max<size_t>(1, bytes / (256 * 1024)));
+        e.pending.store(pieces, std::memory_order_release);
+        const size_t step = kvb::round_up(kvb::ceil_div(bytes, (uint64_t)pieces), 4096);
+        size_t off = 0;
+        int pushed = 0;
+        for (int i = 0; i < pieces; ++i) {
+            const size_t n = off < bytes ? std::min(step, bytes - off) : 0;
+            if (n == 0) { e.pending.fetch_sub(1, std::memory_order_release); continue; }
+            q->workers.push(CopyTask{(char *)dst + off, (const char *)src + off, n, ev, &e.pending});
+            off += n;
+            ++pushed;
+        }
+        (void)pushed;
+    };
+
+    if (offload) {
+        for (size_t c = 0; c < N && err == KV_OK; ++c) {
+            const Chunk &ch = chunks[c];
+            const Span &sp = spans[ch.span];
+            const size_t slot = (size_t)ch.span % n_slots;
+            char *img = staging + slot * slot_bytes;
+            if (ch.first) {
+                // the slot's previous copies must have left it before the kernel overwrites it
+                if ((size_t)ch.span >= n_slots) KV_HIP_BRK(hipStreamWaitEvent(q->s_compute, q->ev_free[slot], 0))
+                time_begin(KV_KERNEL_PACK);
+                err = kv_offload_pack(p, sp.layer, sp.kind, view, sp.seq, sp.tok0, sp.ntok, img, slot_bytes, q->s_compute);
+                time_end();
+                if (err != KV_OK) break;
+                if (stats) { stats->kernel_launches[KV_KERNEL_PACK]++; stats->n_spans++; }
+                KV_HIP_BRK(hipEventRecord(q->ev_ready[slot], q->s_compute));
+                KV_HIP_BRK(hipStreamWaitEvent(q->s_copy, q->ev_ready[slot], 0));
+            }
+            if ((err = acquire(c)) != KV_OK) break;
+            Entry &e = q->ring[c % (size_t)depth];
+            if (sp.path == KV_PATH_DIRECT) {
+                KV_HIP_BRK(hipMemcpyAsync(host_ptr(ch), img + ch.stage_off, ch.bytes, hipMemcpyDeviceToHost, q->s_copy));
+                KV_HIP_BRK(hipEventRecord(e.ev, q->s_copy));
+            } else {
+                KV_HIP_BRK(hipMemcpyAsync(bounce_ptr(c), img + ch.stage_off, ch.bytes, hipMemcpyDeviceToHost, q->s_copy));
+                KV_HIP_BRK(hipEventRecord(e.ev, q->s_copy));
+                fan_out(c, host_ptr(ch), bounce_ptr(c), ch.bytes, e.ev);
+            }
+            max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(c + 1 - n_waited));
+            if (ch.last) KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_copy));
+            if (stats) {
+                stats->n_chunks++;
+                (sp.path == KV_PATH_DIRECT ? stats->bytes_direct : stats->bytes_pagecache) += ch.bytes;
+            }
+        }
+    } else {
+        // Reload.  Page-cache-path chunks are started (arena -> bounce memcpy) a few commands ahead of
+        // their H2D issue; a direct chunk starts when it is issued.
+        const size_t look = std::max<size_t>(1, (size_t)depth / 2);
+        size_t cs = 0;  // next chunk to start
+        for (size_t ci = 0; ci < N && err == KV_OK; ++ci) {
+            while (cs < N && err == KV_OK) {
+                const bool pc = spans[chunks[cs].span].path == KV_PATH_PAGECACHE;
+                if (cs >= ci + (pc ? look : 1)) break;
+                if ((err = acquire(cs)) != KV_OK) break;
+                Entry &e = q->ring[cs % (size_t)depth];
+                if (pc) fan_out(cs, bounce_ptr(cs), host_ptr(chunks[cs]), chunks[cs].bytes, nullptr);
+                else e.pending.store(0, std::memory_order_release);
+                ++cs;
+                max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(cs - n_waited));
+            }
+            if (err != KV_OK) break;
+            const Chunk &ch = chunks[ci];
+            const Span &sp = spans[ch.span];
+            const size_t slot = (size_t)ch.span % n_slots;
+            char *img = staging + slot * slot_bytes;
+            Entry &e = q->ring[ci % (size_t)depth];
+            if (ch.first && (size_t)ch.span >= n_slots) KV_HIP_BRK(hipStreamWaitEvent(q->s_copy, q->ev_free[slot], 0));
+            if (sp.path == KV_PATH_DIRECT) {
+                KV_HIP_BRK(hipMemcpyAsync(img + ch.stage_off, host_ptr(ch), ch.bytes, hipMemcpyHostToDevice, q->s_copy));
+            } else {
+                spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
+                KV_HIP_BRK(hipMemcpyAsync(img + ch.stage_off, bounce_ptr(ci), ch.bytes, hipMemcpyHostToDevice, q->s_copy));
+            }
+            KV_HIP_BRK(hipEventRecord(e.ev, q->s_copy));
+            if (stats) {
+                stats->n_chunks++;
+                (sp.path == KV_PATH_DIRECT ? stats->bytes_direct : stats->bytes_pagecache) += ch.bytes;
+            }
+            if (ch.last) {
+                KV_HIP_BRK(hipEventRecord(q->ev_ready[slot], q->s_copy));
+                KV_HIP_BRK(hipStreamWaitEvent(q->s_compute, q->ev_ready[slot], 0));
+                time_begin(KV_KERNEL_UNPACK);
+                err = kv_reload_unpack(p, sp.layer, sp.kind, img, slot_bytes, view, sp.seq, sp.tok0, sp.ntok, q->s_compute);
+                time_end();
+                if (err != KV_OK) break;
+                if (stats) { stats->kernel_launches[KV_KERNEL_UNPACK]++; stats->n_spans++; }
+                KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_compute));
+                if (dir == KV_DIR_RELOAD_ATTN && sp.last_of_layer) {
+                    time_begin(KV_KERNEL_ATTN_PARTIAL);  // partial + combine bracketed together
+                    err = kv_decode_attn(p, view, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
+                                         attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
+                    time_end();
+                    if (err != KV_OK) break;
+                    if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
+                }
+            }
+        }
+    }
+
+    // Drain: every outstanding command, every kernel, every host copy.
+    hipError_t e1 = hipStreamSynchronize(q->s_copy);
+    hipError_t e2 = hipStreamSynchronize(q->s_compute);
+    for (auto &e : q->ring) spin_until_zero(e.pending);
+    if (err == KV_OK && (e1 != hipSuccess || e2 != hipSuccess)) {
+        kvb::set_hip_error((int)(e1 != hipSuccess ? e1 : e2));
+        err = KV_EHIP;
+    }
+    if (stats) {
+        stats->max_in_flight = max_in_flight;
+        if (time_kernels && err == KV_OK) {
+            for (size_t i = 0; i < timing_kind.size(); ++i) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, q->timing[2 * i], q->timing[2 * i + 1]) == hipSuccess)
+                    stats->kernel_ms[timing_kind[i]] += ms;
+            }
+        }
+        stats->wall_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
+    }
+    return err;
+}

@@ -1,0 +1,170 @@
+"""Host-side logic of the native library against the CPU checker (no GPU needed): the extent
+planner (Alg. 1, Eq. 3-6), token-range translation (Alg. 2), chunk commands (Eq. 7-11), error
+codes, and that the C ABI exports every symbol the header declares."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import kv_oracle as o
+from paper_2604_26557_amd import binding as kv
+from paper_2604_26557_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _plans(cfg, lens=None):
+    lens = W.seq_lens(cfg) if lens is None else lens
+    per_seq = cfg.extent_mode == W.PER_SEQ
+    p = kv.kv_layout_plan(cfg.n_layers, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, lens,
+                          kv.KV_F16 if cfg.dtype == W.F16 else kv.KV_BF16, cfg.sector_bytes, cfg.chunk_tokens,
+                          kv.KV_PER_SEQ if per_seq else kv.KV_TOKEN_MAJOR, cfg.lba_start, kv.KV_UNBOUNDED,
+                          cfg.pc_budget_bytes, kv.KV_UNBOUNDED)
+    ref = o.layout_plan(cfg.n_layers, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, lens, 2, cfg.sector_bytes,
+                        per_seq, cfg.pc_budget_bytes, cfg.lba_start)
+    return p, ref, lens
+
+
+def test_header_symbols_exported():
+    text = open(os.path.join(ROOT, "include", "kvblade.h")).read()
+    declared = set(re.findall(r"\b(kv_[a-z_0-9]+)\s*\(", text))
+    declared -= {n for n in declared if n.endswith("_t")}
+    assert declared == set(kv.EXPORTS)
+    lib = kv.lib()
+    for name in declared:
+        assert hasattr(lib, name)
+    assert lib.kv_abi_version() == 1
+
+
+@pytest.mark.parametrize("idx", range(5))
+def test_plan_matches_oracle_all_configs(idx):
+    cfg = W.CONFIGS[idx]
+    p, ref, lens = _plans(cfg)
+    info = p.info
+    assert info.n_pagecache_layers == ref.n1
+    assert info.row_bytes == ref.row_bytes
+    assert info.tensor_blocks == ref.n_blocks_tensor
+    assert info.tensor_payload_bytes == ref.payload_bytes
+    assert info.region_bytes_needed == (ref.region_bytes if ref.n1 < ref.L else 0)
+    assert info.pageable_bytes_needed == ref.pageable_bytes
+    for layer in range(cfg.n_layers):
+        for kind in (0, 1):
+            n = 2 * layer + kind
+            e = kv.kv_plan_tensor(p, layer, kind)
+            assert (e.path, e.lba_start, e.n_blocks, e.file_off, e.bytes) == \
+                (int(ref.path[n]), int(ref.lba_start[n]), int(ref.n_blocks[n]), int(ref.file_off[n]), ref.payload_bytes)
+    for b in range(len(lens)):
+        assert kv.kv_plan_seq_base(p, b) == int(ref.seq_base[b])
+
+
+def _expected_translate(ref, n, b, tok0, ntok):
+    rc, slba, req = o.token_range(ref, n, b, tok0, ntok)
+    if rc != o.OK:
+        return rc, 0, 0
+    cap = ref.cap[b]
+    sec = ref.lba_size
+    if tok0 + ntok == cap:
+        req = -(-req // sec) * sec          # tail of the extent: rounded up, pad is zeros
+    elif req % sec:
+        return o.EALIGN, 0, 0               # a range may only end inside a sector at the tail
+    return rc, slba, req
+
+
+@pytest.mark.parametrize("idx", [0, 1, 3])
+def test_translate_and_chunks_match_oracle(idx):
+    cfg = W.CONFIGS[idx]
+    if idx == 3:
+        cfg = W.shrink(cfg, n_layers=3, len_range=(100, 700))
+    p, ref, lens = _plans(cfg)
+    rng = np.random.default_rng(idx)
+    nseq = len(lens) if ref.per_seq else 1
+    for layer in sorted({0, cfg.n_layers - 1}):
+        for kind in (0, 1):
+            n = 2 * layer + kind
+            for b in range(nseq):
+                cap = lens[b]
+                cases = [(0, cap), (0, 1), (cap - 1, 1), (0, cfg.chunk_tokens), (cfg.chunk_tokens, cap - cfg.chunk_tokens)]
+                cases += [(int(rng.integers(0, cap)), int(rng.integers(1, cap + 1))) for _ in range(40)]
+                cases = [c for c in cases if c[1] >= 1]
+                for tok0, ntok in cases:
+                    want = _expected_translate(ref, n, b, tok0, ntok)
+                    try:
+                        got = (0,) + kv.kv_plan_translate(p, layer, kind, b, tok0, ntok)
+                    except kv.KVError as e:
+                        got = (e.code, 0, 0)
+                    assert got == want, (layer, kind, b, tok0, ntok)
+                # Eq. 7-11 over the whole (sub-)extent
+                rc, slba, req = o.token_range(ref, n, b, 0, cap)
+                want_cmds = o.chunk_cmds(slba, req, cfg.chunk_tokens * ref.row_bytes, ref.lba_size)
+                got_cmds = kv.kv_plan_chunk_cmds(p, layer, kind, b)
+                assert [(c.slba, c.nlb, c.buf_off) for c in got_cmds] == want_cmds
+                assert [c.tok0 for c in got_cmds] == [i * cfg.chunk_tokens for i in range(len(got_cmds))]
+                assert sum(c.ntok for c in got_cmds) == cap
+
+
+def test_chunk_cmds_other_chunk_sizes():
+    cfg = W.CONFIGS[1]
+    p, ref, lens = _plans(cfg)
+    for C in (2, 64, 1000, 4096, 8192):   # rows are 2 KiB, sectors 4 KiB: C must be even
+        rc, slba, req = o.token_range(ref, 5, 0, 0, lens[0])
+        want = o.chunk_cmds(slba, req, C * ref.row_bytes, ref.lba_size)
+        got = kv.kv_plan_chunk_cmds(p, 2, 1, 0, C)
+        assert [(c.slba, c.nlb, c.buf_off) for c in got] == want
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_plan_chunk_cmds(p, 2, 1, 0, 3)
+    assert e.value.code == kv.KV_EALIGN
+
+
+def test_pagecache_path_addresses_are_arena_sectors():
+    cfg = W.CONFIGS[2]
+    p, ref, lens = _plans(cfg)
+    e = kv.kv_plan_tensor(p, 3, 1)
+    assert e.path == kv.KV_PATH_PAGECACHE and e.file_off == 7 * 64 * W.MiB
+    slba, req = kv.kv_plan_translate(p, 3, 1, 0, 1024, 1024)
+    assert slba * 4096 == e.file_off + 1024 * 2048 and req == 2 * W.MiB
+    e = kv.kv_plan_tensor(p, 16, 0)
+    assert e.path == kv.KV_PATH_DIRECT and e.lba_start == 2048   # numbering skips page-cache tensors
+
+
+def test_error_codes():
+    def plan(**kw):
+        a = dict(n_layers=2, n_kv_heads=2, n_q_heads=4, head_dim=64, seq_cap=[256], dtype=kv.KV_F16,
+                 sector_bytes=512, chunk_tokens=64)
+        a.update(kw)
+        return kv.kv_layout_plan(**a)
+
+    def code(fn):
+        with pytest.raises(kv.KVError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: plan(sector_bytes=1024)) == kv.KV_EINVAL
+    assert code(lambda: plan(dtype=7)) == kv.KV_EINVAL
+    assert code(lambda: plan(n_q_heads=5)) == kv.KV_EINVAL
+    assert code(lambda: plan(head_dim=12)) == kv.KV_EINVAL
+    assert code(lambda: plan(seq_cap=[256, 255])) == kv.KV_EINVAL               # token-major needs a uniform batch
+    assert code(lambda: plan(n_kv_heads=1, head_dim=64, sector_bytes=4096, chunk_tokens=3)) == kv.KV_EALIGN
+    assert code(lambda: plan(lba_start=100, region_blocks=100 + 4 * 128 - 1)) == kv.KV_ENOSPC
+    plan(lba_start=100, region_blocks=100 + 4 * 128).close()
+    assert code(lambda: plan(pc_budget_bytes=2 * 65536, pageable_bytes=2 * 65536 - 1)) == kv.KV_ENOSPC
+    p = plan()
+    assert code(lambda: kv.kv_plan_tensor(p, 2, 0)) == kv.KV_ERANGE
+    assert code(lambda: kv.kv_plan_tensor(p, 0, 2)) == kv.KV_EINVAL
+    assert code(lambda: kv.kv_plan_translate(p, 0, 0, 0, 1, 2)) == kv.KV_EALIGN  # 256 B rows, 512 B sectors
+    assert code(lambda: kv.kv_plan_translate(p, 0, 0, 0, 0, 3)) == kv.KV_EALIGN  # ends inside a sector, not at tail
+    assert code(lambda: kv.kv_plan_translate(p, 0, 0, 0, 250, 8)) == kv.KV_ERANGE
+    assert code(lambda: kv.kv_plan_translate(p, 0, 0, 0, 0, 0)) == kv.KV_EINVAL
+    assert code(lambda: kv.kv_plan_translate(p, 0, 0, 1, 0, 2)) == kv.KV_ERANGE  # no sequence 1 in token-major
+    assert kv.kv_plan_translate(p, 0, 0, 0, 254, 2) == (2048 * 0 + 254 * 256 // 512, 512)
+    assert kv.lib().kv_strerror(kv.KV_EALIGN).decode().startswith("offset")
+
+
+def test_odd_tail_rounds_up():
+    """8 KV heads, D=128, batch 1 under 4 KiB sectors: 2 KiB rows, an odd capacity pads half a sector."""
+    p = kv.kv_layout_plan(1, 8, 32, 128, [4097], kv.KV_F16, 4096, 256, kv.KV_TOKEN_MAJOR, 2048)
+    assert p.info.tensor_blocks == 2049
+    slba, req = kv.kv_plan_translate(p, 0, 1, 0, 4096, 1)
+    assert slba == 2048 + 2049 + 2048 and req == 4096
+    cmds = kv.kv_plan_chunk_cmds(p, 0, 0, 0)
+    assert len(cmds) == 17 and cmds[-1].nlb == 0 and cmds[-1].ntok == 1
