@@ -97,6 +97,10 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2604_26557_amd.build`")
+        # PyTorch ships its own copy of the HIP runtime under the same soname.  Device memory and
+        # streams come from PyTorch, so its copy must be the one in the process: import it first,
+        # and this library's dependency then resolves to the runtime that is already loaded.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i = C.c_void_p, C.c_int
         L.kv_layout_plan.argtypes = [C.POINTER(kv_plan_desc_t), C.POINTER(vp)]

@@ -1,0 +1,328 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU checker, element by element, on
+reduced shapes of the five evaluation configs that still span several tiles and a ragged tail.
+Pack / unpack / host-region bytes must be bit-exact; attention within 2e-3 max abs error of the fp64
+reference (and 1e-2 of the reference's own max magnitude, so the check is not vacuous)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_oracle as o
+from paper_2604_26557_amd import binding as kv
+from paper_2604_26557_amd import workloads as W
+from kvcase import Case, bits, pinned_bytes
+
+pytestmark = pytest.mark.gpu
+
+ATTN_ATOL = 2e-3
+ATTN_REL_OF_MAX = 1e-2
+GUARD = 4096
+CANARY = 0xA5
+
+
+def small_configs():
+    c = W.CONFIGS
+    return [
+        c[0],
+        W.shrink(c[1], n_layers=3, seq_len=1001),
+        W.shrink(c[2], n_layers=4, seq_len=3000, pc_budget_bytes=2 * 2 * 3000 * 2048),
+        W.shrink(c[3], n_layers=3, batch=4, len_range=(100, 1500)),
+        W.shrink(c[4], n_layers=3, seq_len=600, pc_budget_bytes=1 * 2 * 600 * 32768),
+        # shapes outside the five: odd head count (row of 5*8 vectors), B=3 token-major, 512 B sectors
+        W.KVConfig("odd_heads", 7, 2, 5, 10, 64, 3, W.F16, 512, 4, 2, W.TOKEN_MAJOR, W.BHSD, 203),
+        # token-major extent from a paged source, G = 8
+        W.KVConfig("paged_token_major", 8, 2, 1, 8, 128, 2, W.BF16, 4096, 32, 2, W.TOKEN_MAJOR, W.PAGED, 320),
+    ]
+
+
+SMALL = small_configs()
+IDS = [c.name for c in SMALL]
+
+
+@pytest.fixture(scope="module", params=SMALL, ids=IDS)
+def case(request):
+    torch.cuda.set_device(0)
+    return Case(request.param, "cuda", gen_device="cpu")
+
+
+def _guarded(nbytes):
+    buf = torch.full((nbytes + 2 * GUARD,), CANARY, dtype=torch.uint8, device="cuda")
+    return buf, buf[GUARD:GUARD + nbytes]
+
+
+def _guards_intact(buf, nbytes):
+    b = buf.cpu().numpy()
+    return (b[:GUARD] == CANARY).all() and (b[GUARD + nbytes:] == CANARY).all()
+
+
+# ------------------------------------------------------------------------------------------ pack
+def test_pack_whole_tensor(case):
+    r = case.ref
+    nbytes = r.n_blocks_tensor * r.lba_size
+    for layer in sorted({0, case.cfg.n_layers - 1}):
+        for kind in (0, 1):
+            buf, dst = _guarded(nbytes)
+            kv.kv_offload_pack(case.plan, layer, kind, case.view, kv.KV_SEQ_ALL, 0, 0, dst)
+            torch.cuda.synchronize()
+            assert np.array_equal(dst.cpu().numpy(), case.expected_extent(layer, kind)), (layer, kind)
+            assert _guards_intact(buf, nbytes)
+
+
+def test_pack_chunk_ranges(case):
+    r = case.ref
+    layer, kind = case.cfg.n_layers - 1, 1
+    want = case.expected_extent(layer, kind)
+    nseq = len(case.lens) if r.per_seq else 1
+    for b in range(nseq):
+        base = int(r.seq_base[b]) * r.lba_size
+        for c in kv.kv_plan_chunk_cmds(case.plan, layer, kind, b):
+            nbytes = (c.nlb + 1) * r.lba_size
+            buf, dst = _guarded(nbytes)
+            kv.kv_offload_pack(case.plan, layer, kind, case.view, b, c.tok0, c.ntok, dst)
+            torch.cuda.synchronize()
+            got = dst.cpu().numpy()
+            assert np.array_equal(got, want[base + c.buf_off: base + c.buf_off + nbytes]), (b, c.tok0)
+            assert _guards_intact(buf, nbytes)
+
+
+# ------------------------------------------------------------------------------------------ unpack
+def _check_restored(case, k_new, v_new, layers, fill=0x7E7E):
+    cfg = case.cfg
+    for layer in layers:
+        for kind, new in ((0, k_new), (1, v_new)):
+            got, src = bits(new[layer]), bits(case.tensor_cpu(layer, kind))
+            if case.paged:
+                bt = cfg.block_tokens
+                table = case.table_cpu.numpy()
+                touched = np.zeros(got.shape[:1] + got.shape[2:3], dtype=bool)   # [n_pool, bt]
+                for b, n in enumerate(case.lens):
+                    for s in range(n):
+                        touched[table[b, s // bt], s % bt] = True
+                m = touched[:, None, :, None]
+                assert np.array_equal(np.where(m, got, 0), np.where(m, src, 0))
+                assert (np.where(m, fill, got) == fill).all()                     # other slots untouched
+            else:
+                for b, n in enumerate(case.lens):
+                    assert np.array_equal(got[b, :, :n], src[b, :, :n])
+                    assert (got[b, :, n:] == fill).all()
+
+
+def test_unpack_whole_tensor(case):
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    layers = sorted({0, case.cfg.n_layers - 1})
+    for layer in layers:
+        for kind in (0, 1):
+            ext = torch.from_numpy(case.expected_extent(layer, kind)).cuda()
+            kv.kv_reload_unpack(case.plan, layer, kind, ext, view, kv.KV_SEQ_ALL, 0, 0)
+    torch.cuda.synchronize()
+    _check_restored(case, k_new, v_new, layers)
+
+
+def test_unpack_chunk_ranges(case):
+    r = case.ref
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    layer = 0
+    nseq = len(case.lens) if r.per_seq else 1
+    for kind in (0, 1):
+        ext = case.expected_extent(layer, kind)
+        for b in range(nseq):
+            base = int(r.seq_base[b]) * r.lba_size
+            for c in kv.kv_plan_chunk_cmds(case.plan, layer, kind, b):
+                nbytes = (c.nlb + 1) * r.lba_size
+                img = torch.from_numpy(ext[base + c.buf_off: base + c.buf_off + nbytes].copy()).cuda()
+                kv.kv_reload_unpack(case.plan, layer, kind, img, view, b, c.tok0, c.ntok)
+    torch.cuda.synchronize()
+    _check_restored(case, k_new, v_new, [layer])
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[3], SMALL[5]], ids=lambda c: c.name)
+def test_round_trip_raw_bit_patterns(cfg):
+    """Pack is a byte move: NaN / Inf / denormal payloads must survive unchanged."""
+    case = Case(cfg, "cuda", raw=True, gen_device="cpu", s_extra=3)
+    r = case.ref
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    nbytes = r.n_blocks_tensor * r.lba_size
+    for layer in range(cfg.n_layers):
+        for kind in (0, 1):
+            buf, dst = _guarded(nbytes)
+            kv.kv_offload_pack(case.plan, layer, kind, case.view, kv.KV_SEQ_ALL, 0, 0, dst)
+            torch.cuda.synchronize()
+            assert np.array_equal(dst.cpu().numpy(), case.expected_extent(layer, kind))
+            kv.kv_reload_unpack(case.plan, layer, kind, dst, view, kv.KV_SEQ_ALL, 0, 0)
+    torch.cuda.synchronize()
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+
+
+def test_pack_shorter_than_capacity_zero_fills():
+    """Valid length below the extent capacity: rows [0,len) then zeros to the end of the extent."""
+    cfg = W.shrink(W.CONFIGS[0], seq_len=256)
+    case = Case(cfg, "cuda", gen_device="cpu")
+    lens = [100]
+    view = kv.bhsd_view(case.k, case.v, lens, case.lens_dev)
+    r = case.ref
+    nbytes = r.n_blocks_tensor * r.lba_size
+    buf, dst = _guarded(nbytes)
+    kv.kv_offload_pack(case.plan, 1, 0, view, kv.KV_SEQ_ALL, 0, 0, dst)
+    torch.cuda.synchronize()
+    want = np.zeros(nbytes, dtype=np.uint8)
+    t = case.k_cpu[1]
+    o.pack(case.source(t), o.u16(t), False, lens, r.seq_base, r.n_blocks_tensor, r.lba_size, want)
+    assert np.array_equal(dst.cpu().numpy(), want) and not want[100 * 256:].any()
+    assert _guards_intact(buf, nbytes)
+
+
+def test_kernel_argument_errors(case):
+    """Bad arguments are rejected on the host before anything is launched."""
+    r = case.ref
+    dst = torch.zeros(r.n_blocks_tensor * r.lba_size, dtype=torch.uint8, device="cuda")
+
+    def code(fn):
+        with pytest.raises(kv.KVError) as e:
+            fn()
+        return e.value.code
+
+    cap = case.lens[0]
+    assert code(lambda: kv.kv_offload_pack(case.plan, 99, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst)) == kv.KV_ERANGE
+    assert code(lambda: kv.kv_offload_pack(case.plan, 0, 2, case.view, kv.KV_SEQ_ALL, 0, 0, dst)) == kv.KV_EINVAL
+    assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, 0, 0, cap + 1, dst)) == kv.KV_ERANGE
+    assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst[:4096])) == kv.KV_ENOSPC
+    assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst[8:])) == kv.KV_EINVAL
+    if (r.row_bytes % r.lba_size) != 0 and cap > 2:
+        assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, 0, 1, 1, dst)) == kv.KV_EALIGN
+
+
+# ------------------------------------------------------------------------------------------ attention
+def _attn_check(got: torch.Tensor, want: np.ndarray):
+    g = got.double().cpu().numpy()
+    err = np.abs(g - want).max()
+    scale = np.abs(want).max()
+    assert err <= ATTN_ATOL, err
+    assert err <= ATTN_REL_OF_MAX * scale, (err, scale)
+
+
+@pytest.mark.parametrize("n_splits", [0, 1, 3])
+def test_decode_attention(case, n_splits):
+    cfg = case.cfg
+    max_len = max(case.lens)
+    ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, n_splits, max_len), dtype=torch.uint8, device="cuda")
+    for layer in sorted({0, cfg.n_layers - 1}):
+        q = W.query(cfg, layer, "cpu")
+        qd = q.cuda()
+        out = torch.full((len(case.lens), cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        kv.kv_decode_attn(case.plan, case.view, layer, qd, out, kv.KV_OUT_F32, n_splits, ws)
+        torch.cuda.synchronize()
+        _attn_check(out, case.expected_attention(layer, q))
+
+
+def test_decode_attention_16bit_output_and_short_lengths(case):
+    """Output in the KV dtype is the fp32 result rounded to nearest even; a zero-length sequence gives zeros."""
+    cfg = case.cfg
+    lens = list(case.lens)
+    lens[0] = 1
+    if len(lens) > 1:
+        lens[1] = 0
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    view = (kv.paged_view(case.k, case.v, case.table_dev, lens, lens_dev) if case.paged
+            else kv.bhsd_view(case.k, case.v, lens, lens_dev))
+    ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, 0, max(lens)), dtype=torch.uint8, device="cuda")
+    q = W.query(cfg, 0, "cpu")
+    shape = (len(lens), cfg.n_q_heads, cfg.head_dim)
+    out32 = torch.empty(shape, dtype=torch.float32, device="cuda")
+    out16 = torch.empty(shape, dtype=cfg.torch_dtype, device="cuda")
+    kv.kv_decode_attn(case.plan, view, 0, q.cuda(), out32, kv.KV_OUT_F32, 0, ws)
+    kv.kv_decode_attn(case.plan, view, 0, q.cuda(), out16, kv.KV_OUT_SAME, 0, ws)
+    torch.cuda.synchronize()
+    K, V = case.k_cpu[0], case.v_cpu[0]
+    want = o.attention(case.source(K), o.u16(K), o.u16(V), o.u16(q), cfg.dtype == W.BF16, lens, cfg.n_q_heads)
+    _attn_check(out32, want)
+    assert torch.equal(out16, out32.to(cfg.torch_dtype))
+    if len(lens) > 1:
+        assert not out32[1].any()
+
+
+# ------------------------------------------------------------------------------------------ pipeline
+@pytest.mark.parametrize("span_chunks,depth", [(0, 3), (1, 2), (2, 4), (0, 1)])
+def test_pipeline_offload_reload(case, span_chunks, depth):
+    cfg, r = case.cfg, case.ref
+    FILL = 0xC3
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena,
+                            depth=depth, span_chunks=span_chunks)
+    want_region, want_arena = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    assert st.max_in_flight <= depth and st.n_chunks > 0
+    assert st.bytes_direct == r.direct_blocks * r.lba_size and st.bytes_pagecache == r.pageable_bytes
+
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, cfg.n_layers, view, region, arena,
+                            depth=depth, span_chunks=span_chunks)
+    assert st.max_in_flight <= depth
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+
+
+@pytest.mark.parametrize("span_chunks", [0, 1])
+def test_pipeline_reload_attention(case, span_chunks):
+    cfg, r = case.cfg, case.ref
+    region = pinned_bytes(r.region_bytes, 0)
+    arena = np.zeros(max(r.pageable_bytes, 1), dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=cfg.depth)
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    qs = [W.query(cfg, l, "cpu") for l in range(cfg.n_layers)]
+    qd = [q.cuda() for q in qs]
+    outs = [torch.full((len(case.lens), cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+            for _ in range(cfg.n_layers)]
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, view, region, arena,
+                            depth=cfg.depth, q_layers=qd, out_layers=outs, span_chunks=span_chunks, time_kernels=True)
+    assert st.kernel_launches[kv.KV_KERNEL_ATTN_PARTIAL] == cfg.n_layers
+    for l in range(cfg.n_layers):
+        _attn_check(outs[l], case.expected_attention(l, qs[l]))
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+
+
+def test_pipeline_layer_subrange_and_other_chunk_size(case):
+    """Only the requested layers move; a different (aligned) chunk size gives the same bytes."""
+    cfg, r = case.cfg, case.ref
+    if cfg.n_layers < 3:
+        pytest.skip("needs 3 layers")
+    FILL = 0x5A
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    sec_rows = max(1, r.lba_size // r.row_bytes)
+    C = 3 * sec_rows * 8
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 1, 3, case.view, region, arena, chunk_tokens=C, depth=2)
+    want_region, want_arena = case.expected_host(layers=[1, 2], fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+
+
+def test_pipeline_argument_errors(case):
+    cfg, r = case.cfg, case.ref
+    region = pinned_bytes(r.region_bytes, 0)
+    arena = np.zeros(max(r.pageable_bytes, 1), dtype=np.uint8)
+
+    def code(**kw):
+        a = dict(plan=case.plan, direction=kv.KV_DIR_OFFLOAD, layer_begin=0, layer_end=cfg.n_layers, view=case.view,
+                 lba_region=region, pageable=arena, depth=2)
+        a.update(kw)
+        with pytest.raises(kv.KVError) as e:
+            kv.kv_pipeline_run(**a)
+        return e.value.code
+
+    assert code(depth=0) == kv.KV_EINVAL
+    assert code(direction=9) == kv.KV_EINVAL
+    assert code(layer_end=cfg.n_layers + 1) == kv.KV_ERANGE
+    assert code(direction=kv.KV_DIR_RELOAD_ATTN) == kv.KV_EINVAL            # no attention arguments
+    if r.n1 < r.L:
+        assert code(lba_region=region[:r.region_bytes - 1]) == kv.KV_ENOSPC
+        unpinned = torch.zeros(r.region_bytes, dtype=torch.uint8)
+        assert code(lba_region=unpinned) == kv.KV_EINVAL                     # the LBA region must be pinned
+    if r.n1 > 0:
+        assert code(pageable=arena[:r.pageable_bytes - 1]) == kv.KV_ENOSPC
+    if r.row_bytes % r.lba_size:
+        assert code(chunk_tokens=1) == kv.KV_EALIGN
