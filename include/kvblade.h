@@ -149,11 +149,18 @@ typedef struct kv_attn_args {
 
 #define KV_PIPE_TIME_KERNELS 1u /* bracket every kernel with hipEvents and fill kernel_ms */
 
+#define KV_COPY_AUTO 0   /* D2H: copy kernel; H2D: hipMemcpyAsync (the faster of the two, as measured) */
+#define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
+#define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
+
 typedef struct kv_pipe_opts {
     int32_t span_chunks;  /* chunks per kernel launch and staging slot; 0 = a whole tensor */
     int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
     uint32_t flags;       /* KV_PIPE_* */
-    int32_t reserved;
+    int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (2 D2H, 4 H2D);
+                             never more than depth */
+    int32_t d2h_mode;     /* KV_COPY_* for offload transfers */
+    int32_t h2d_mode;     /* KV_COPY_* for reload transfers */
 } kv_pipe_opts_t;
 
 typedef struct kv_pipe_stats {

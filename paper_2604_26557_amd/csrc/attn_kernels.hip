@@ -224,21 +224,57 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
     return (unsigned short)(u >> 16);
 }
 
-// out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup per (hq, b), one thread per d.
-__global__ void kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-                                       void *__restrict__ out, int Hq, int D, int n_splits, int out_mode)
+// out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup of 256 threads per (hq, b).  The split weights
+// exp2(m_s - M) are computed once, in parallel over the splits, and kept in LDS; then thread d sums
+// its column over the splits with independent (pipelined) loads.
+constexpr int kCombineThreads = 256;
+constexpr int kMaxSplits = 1024;
+
+__global__ void __launch_bounds__(kCombineThreads)
+kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restrict__ part_ml,
+                       void *__restrict__ out, int Hq, int D, int n_splits, int out_mode)
 {
-    const int hq = blockIdx.x, b = blockIdx.y;
+    __shared__ float w[kMaxSplits];
+    __shared__ float red[kCombineThreads / 64];
+    __shared__ float sh_M, sh_L;
+    const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const long long o = ((long long)b * Hq + hq) * n_splits;
-    float M = kEmptyMax;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[(o + s) * 2]);
-    for (int d = threadIdx.x; d < D; d += blockDim.x) {
-        float L = 0.f, A = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const float a = exp2f(part_ml[(o + s) * 2] - M);
-            L += part_ml[(o + s) * 2 + 1] * a;
-            A += part_acc[(o + s) * D + d] * a;
-        }
+
+    float mx = kEmptyMax;
+    for (int s = tid; s < n_splits; s += kCombineThreads) mx = fmaxf(mx, part_ml[(o + s) * 2]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    if (tid == 0) {
+        float M = red[0];
+        for (int i = 1; i < kCombineThreads / 64; ++i) M = fmaxf(M, red[i]);
+        sh_M = M;
+    }
+    __syncthreads();
+    const float M = sh_M;
+    float lsum = 0.f;
+    for (int s = tid; s < n_splits; s += kCombineThreads) {
+        const float a = exp2f(part_ml[(o + s) * 2] - M);
+        w[s] = a;
+        lsum += part_ml[(o + s) * 2 + 1] * a;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off);
+    __syncthreads();  // red is reused
+    if ((tid & 63) == 0) red[tid >> 6] = lsum;
+    __syncthreads();
+    if (tid == 0) {
+        float L = 0.f;
+        for (int i = 0; i < kCombineThreads / 64; ++i) L += red[i];
+        sh_L = L;
+    }
+    __syncthreads();
+    const float L = sh_L;
+    for (int d = tid; d < D; d += kCombineThreads) {
+        float A = 0.f;
+#pragma unroll 8
+        for (int s = 0; s < n_splits; ++s) A = fmaf(part_acc[(o + s) * D + d], w[s], A);
         const float r = L > 0.f ? A / L : 0.f;
         const long long oi = ((long long)b * Hq + hq) * D + d;
         if (out_mode == 0) ((float *)out)[oi] = r;
@@ -306,7 +342,7 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
 {
     if (!p || !kv || !q || !out || !workspace) return KV_EINVAL;
     if (out_dtype != KV_OUT_F32 && out_dtype != KV_OUT_SAME) return KV_EINVAL;
-    if (n_splits < 0 || n_splits > 65535) return KV_EINVAL;
+    if (n_splits < 0 || n_splits > kMaxSplits) return KV_EINVAL;
     if (p->D != 64 && p->D != 128 && p->D != 256) return KV_EINVAL;
     if (!kv->k_layers || !kv->v_layers || !kv->seq_lens_host || !kv->seq_lens_dev) return KV_EINVAL;
     if (layer < 0 || layer >= p->L || layer >= kv->n_layers) return KV_ERANGE;
@@ -373,7 +409,7 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
 
     const int out_mode = out_dtype == KV_OUT_F32 ? 0 : (bf16 ? 2 : 1);
-    hipLaunchKernelGGL(kv_attn_combine_kernel, dim3((unsigned)p->Hq, (unsigned)p->B), dim3(std::min(p->D, 256)), 0,
+    hipLaunchKernelGGL(kv_attn_combine_kernel, dim3((unsigned)p->Hq, (unsigned)p->B), dim3(kCombineThreads), 0,
                        st, a.part_acc, a.part_ml, out, p->Hq, p->D, ns, out_mode);
     e = hipGetLastError();
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }

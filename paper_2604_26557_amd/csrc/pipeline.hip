@@ -9,8 +9,12 @@
 //  * Kernels run per span = a whole tensor by default (HBM is large, so staging a whole extent costs
 //    nothing and the pack / unpack launches are big enough to run at HBM speed), or every
 //    `span_chunks` chunks on request.
-// Streams: one for kernels, one for copies; events order pack -> D2H and H2D -> unpack -> attention
-// and guard staging-slot reuse.  All streams keep the default priority.
+// Streams: one for kernels and up to four for copies (chunk c goes to copy stream c mod n, so the
+// start-up and tail of one transfer hide behind the next); events order pack -> D2H and
+// H2D -> unpack -> attention and guard staging-slot reuse.  All streams keep the default priority.
+// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D is fastest as
+// hipMemcpyAsync over four streams; D2H is fastest as this file's own copy kernel over two streams
+// (the runtime's per-command cost dominates D2H copies of a few hundred KiB).  Both are options.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -43,6 +47,38 @@ namespace {
             kvb::set_hip_error((int)e_);                   \
             err = KV_EHIP;                                 \
             break;                                         \
+        }                                                  \
+    }
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// One chunk command executed by the shader engines: 16-byte vectors, four loads in flight per lane.
+// Either side may be pinned host memory (mapped into the device address space at its host address).
+__global__ void __launch_bounds__(256)
+kv_chunk_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t nvec)
+{
+    constexpr int U = 4;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + (U - 1) * stride < nvec; i += U * stride) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+    }
+    for (; i < nvec; i += stride) dst[i] = src[i];
+}
+
+constexpr int kMaxCopyStreams = 4;
+
+// Same without leaving the loop (for use inside nested loops; the caller tests err).
+#define KV_HIP_SET(call)                                   \
+    {                                                      \
+        hipError_t e_ = (call);                            \
+        if (e_ != hipSuccess) {                            \
+            kvb::set_hip_error((int)e_);                   \
+            err = KV_EHIP;                                 \
         }                                                  \
     }
 
@@ -134,14 +170,16 @@ struct Entry {
 
 struct kv_pipeline {
     int device = 0;
-    hipStream_t s_compute = nullptr, s_copy = nullptr;
+    hipStream_t s_compute = nullptr;
+    hipStream_t s_copy[kMaxCopyStreams] = {nullptr, nullptr, nullptr, nullptr};
     void *staging = nullptr;
     size_t staging_bytes = 0;
     void *bounce = nullptr;
     size_t bounce_bytes = 0;
     void *attn_ws = nullptr;
     size_t attn_ws_bytes = 0;
-    std::vector<hipEvent_t> ev_ready, ev_free;  // per staging slot
+    std::vector<hipEvent_t> ev_ready, ev_free;  // per staging slot, recorded on the kernel stream
+    std::vector<hipEvent_t> ev_done;            // per staging slot and copy stream
     std::vector<Entry> ring;                    // per in-flight command
     std::vector<hipEvent_t> timing;             // pairs
     Workers workers;
@@ -150,16 +188,17 @@ struct kv_pipeline {
     {
         workers.stop();
         (void)hipSetDevice(device);
-        if (s_copy) (void)hipStreamSynchronize(s_copy);
+        for (auto st : s_copy) if (st) (void)hipStreamSynchronize(st);
         if (s_compute) (void)hipStreamSynchronize(s_compute);
         for (auto e : ev_ready) (void)hipEventDestroy(e);
         for (auto e : ev_free) (void)hipEventDestroy(e);
+        for (auto e : ev_done) (void)hipEventDestroy(e);
         for (auto &e : ring) if (e.ev) (void)hipEventDestroy(e.ev);
         for (auto e : timing) (void)hipEventDestroy(e);
         if (staging) (void)hipFree(staging);
         if (bounce) (void)hipHostFree(bounce);
         if (attn_ws) (void)hipFree(attn_ws);
-        if (s_copy) (void)hipStreamDestroy(s_copy);
+        for (auto st : s_copy) if (st) (void)hipStreamDestroy(st);
         if (s_compute) (void)hipStreamDestroy(s_compute);
     }
 };
@@ -183,7 +222,7 @@ int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, si
         p->pipe = new kv_pipeline();
         KV_HIP(hipGetDevice(&p->pipe->device));
         KV_HIP(hipStreamCreateWithFlags(&p->pipe->s_compute, hipStreamNonBlocking));
-        KV_HIP(hipStreamCreateWithFlags(&p->pipe->s_copy, hipStreamNonBlocking));
+        for (auto &st : p->pipe->s_copy) KV_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
     }
     kv_pipeline *q = p->pipe;
     const size_t need = n_slots * slot_bytes;
@@ -208,6 +247,8 @@ int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, si
     int rc = ensure_events(q->ev_ready, n_slots, hipEventDisableTiming);
     if (rc) return rc;
     rc = ensure_events(q->ev_free, n_slots, hipEventDisableTiming);
+    if (rc) return rc;
+    rc = ensure_events(q->ev_done, n_slots * kMaxCopyStreams, hipEventDisableTiming);
     if (rc) return rc;
     if (q->ring.size() < (size_t)depth) {
         std::vector<Entry> bigger((size_t)depth);
@@ -256,6 +297,16 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const int n_workers = opts && opts->host_workers > 0 ? opts->host_workers : 8;
     const bool time_kernels = opts && (opts->flags & KV_PIPE_TIME_KERNELS);
     if (span_chunks < 0 || n_workers > 64) return KV_EINVAL;
+    const bool offload_dir = dir == KV_DIR_OFFLOAD;
+    int ns = opts ? opts->copy_streams : 0;
+    if (ns < 0 || ns > kMaxCopyStreams) return KV_EINVAL;
+    const int d2h_mode = opts ? opts->d2h_mode : KV_COPY_AUTO, h2d_mode = opts ? opts->h2d_mode : KV_COPY_AUTO;
+    if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
+        return KV_EINVAL;
+    const bool d2h_kernel = d2h_mode != KV_COPY_MEMCPY;  // auto: copy kernel
+    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;  // auto: hipMemcpyAsync
+    if (ns == 0) ns = offload_dir ? 2 : 4;
+    ns = std::min(ns, depth);
     if (stats) std::memset(stats, 0, sizeof(*stats));
     if (layer_begin == layer_end) return KV_OK;
 
@@ -268,7 +319,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     bool any_direct = false, any_pc = false;
     for (int l = layer_begin; l < layer_end; ++l) (l < p->n1 ? any_pc : any_direct) = true;
     if (any_direct) {
-        if (!lba_region) return KV_EINVAL;
+        if (!lba_region || ((uintptr_t)lba_region & 15)) return KV_EINVAL;
         if (region_bytes < p->region_bytes_needed) return KV_ENOSPC;
         hipPointerAttribute_t at;
         hipError_t e = hipPointerGetAttributes(&at, lba_region);
@@ -360,8 +411,9 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         (void)hipEventRecord(q->timing[2 * (timing_kind.size() - 1) + 1], q->s_compute);
     };
 
-    const bool offload = dir == KV_DIR_OFFLOAD;
+    const bool offload = offload_dir;
     const size_t N = chunks.size();
+    std::vector<unsigned> slot_used(n_slots, 0u);  // copy streams that carried the slot's last span
     size_t n_waited = 0;  // chunks [0, n_waited) are known complete
     uint32_t max_in_flight = 0;
     int err = KV_OK;
@@ -402,6 +454,18 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         (void)pushed;
     };
 
+    // Transfer of one chunk command on copy stream `st`.
+    auto issue_copy = [&](void *dst, const void *src, size_t bytes, bool to_host, hipStream_t st) -> hipError_t {
+        const bool by_kernel = to_host ? d2h_kernel : h2d_kernel;
+        if (!by_kernel)
+            return hipMemcpyAsync(dst, src, bytes, to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, st);
+        const size_t nvec = bytes / 16;
+        const unsigned blocks = (unsigned)std::min<size_t>(256, std::max<size_t>(1, nvec / (256 * 4)));
+        hipLaunchKernelGGL(kv_chunk_copy_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4 *)src, (u32x4 *)dst, nvec);
+        return hipGetLastError();
+    };
+    unsigned used = 0;  // copy streams that carried a chunk of the current span
+
     if (offload) {
         for (size_t c = 0; c < N && err == KV_OK; ++c) {
             const Chunk &ch = chunks[c];
@@ -410,27 +474,40 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             char *img = staging + slot * slot_bytes;
             if (ch.first) {
                 // the slot's previous copies must have left it before the kernel overwrites it
-                if ((size_t)ch.span >= n_slots) KV_HIP_BRK(hipStreamWaitEvent(q->s_compute, q->ev_free[slot], 0))
+                if ((size_t)ch.span >= n_slots)
+                    for (int s = 0; s < ns && err == KV_OK; ++s)
+                        if (slot_used[slot] >> s & 1) KV_HIP_SET(hipStreamWaitEvent(q->s_compute, q->ev_done[slot * kMaxCopyStreams + s], 0));
+                if (err != KV_OK) break;
                 time_begin(KV_KERNEL_PACK);
                 err = kv_offload_pack(p, sp.layer, sp.kind, view, sp.seq, sp.tok0, sp.ntok, img, slot_bytes, q->s_compute);
                 time_end();
                 if (err != KV_OK) break;
                 if (stats) { stats->kernel_launches[KV_KERNEL_PACK]++; stats->n_spans++; }
                 KV_HIP_BRK(hipEventRecord(q->ev_ready[slot], q->s_compute));
-                KV_HIP_BRK(hipStreamWaitEvent(q->s_copy, q->ev_ready[slot], 0));
+                used = 0;
             }
             if ((err = acquire(c)) != KV_OK) break;
             Entry &e = q->ring[c % (size_t)depth];
+            const int s = (int)(c % (size_t)ns);
+            hipStream_t st = q->s_copy[s];
+            if (!(used >> s & 1)) {  // first chunk of this span on this stream: order it after the pack
+                KV_HIP_BRK(hipStreamWaitEvent(st, q->ev_ready[slot], 0));
+                used |= 1u << s;
+            }
             if (sp.path == KV_PATH_DIRECT) {
-                KV_HIP_BRK(hipMemcpyAsync(host_ptr(ch), img + ch.stage_off, ch.bytes, hipMemcpyDeviceToHost, q->s_copy));
-                KV_HIP_BRK(hipEventRecord(e.ev, q->s_copy));
+                KV_HIP_BRK(issue_copy(host_ptr(ch), img + ch.stage_off, ch.bytes, true, st));
+                KV_HIP_BRK(hipEventRecord(e.ev, st));
             } else {
-                KV_HIP_BRK(hipMemcpyAsync(bounce_ptr(c), img + ch.stage_off, ch.bytes, hipMemcpyDeviceToHost, q->s_copy));
-                KV_HIP_BRK(hipEventRecord(e.ev, q->s_copy));
+                KV_HIP_BRK(issue_copy(bounce_ptr(c), img + ch.stage_off, ch.bytes, true, st));
+                KV_HIP_BRK(hipEventRecord(e.ev, st));
                 fan_out(c, host_ptr(ch), bounce_ptr(c), ch.bytes, e.ev);
             }
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(c + 1 - n_waited));
-            if (ch.last) KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_copy));
+            if (ch.last) {
+                for (int k = 0; k < ns && err == KV_OK; ++k)
+                    if (used >> k & 1) KV_HIP_SET(hipEventRecord(q->ev_done[slot * kMaxCopyStreams + k], q->s_copy[k]));
+                slot_used[slot] = used;
+            }
             if (stats) {
                 stats->n_chunks++;
                 (sp.path == KV_PATH_DIRECT ? stats->bytes_direct : stats->bytes_pagecache) += ch.bytes;
@@ -458,21 +535,31 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             const size_t slot = (size_t)ch.span % n_slots;
             char *img = staging + slot * slot_bytes;
             Entry &e = q->ring[ci % (size_t)depth];
-            if (ch.first && (size_t)ch.span >= n_slots) KV_HIP_BRK(hipStreamWaitEvent(q->s_copy, q->ev_free[slot], 0));
+            const int s = (int)(ci % (size_t)ns);
+            hipStream_t st = q->s_copy[s];
+            if (ch.first) used = 0;
+            if (!(used >> s & 1)) {  // first chunk of this span on this stream: the slot must be free
+                if ((size_t)ch.span >= n_slots) KV_HIP_BRK(hipStreamWaitEvent(st, q->ev_free[slot], 0));
+                used |= 1u << s;
+            }
             if (sp.path == KV_PATH_DIRECT) {
-                KV_HIP_BRK(hipMemcpyAsync(img + ch.stage_off, host_ptr(ch), ch.bytes, hipMemcpyHostToDevice, q->s_copy));
+                KV_HIP_BRK(issue_copy(img + ch.stage_off, host_ptr(ch), ch.bytes, false, st));
             } else {
                 spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
-                KV_HIP_BRK(hipMemcpyAsync(img + ch.stage_off, bounce_ptr(ci), ch.bytes, hipMemcpyHostToDevice, q->s_copy));
+                KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st));
             }
-            KV_HIP_BRK(hipEventRecord(e.ev, q->s_copy));
+            KV_HIP_BRK(hipEventRecord(e.ev, st));
             if (stats) {
                 stats->n_chunks++;
                 (sp.path == KV_PATH_DIRECT ? stats->bytes_direct : stats->bytes_pagecache) += ch.bytes;
             }
             if (ch.last) {
-                KV_HIP_BRK(hipEventRecord(q->ev_ready[slot], q->s_copy));
-                KV_HIP_BRK(hipStreamWaitEvent(q->s_compute, q->ev_ready[slot], 0));
+                for (int k = 0; k < ns && err == KV_OK; ++k) {
+                    if (!(used >> k & 1)) continue;
+                    KV_HIP_SET(hipEventRecord(q->ev_done[slot * kMaxCopyStreams + k], q->s_copy[k]));
+                    if (err == KV_OK) KV_HIP_SET(hipStreamWaitEvent(q->s_compute, q->ev_done[slot * kMaxCopyStreams + k], 0));
+                }
+                if (err != KV_OK) break;
                 time_begin(KV_KERNEL_UNPACK);
                 err = kv_reload_unpack(p, sp.layer, sp.kind, img, slot_bytes, view, sp.seq, sp.tok0, sp.ntok, q->s_compute);
                 time_end();
@@ -492,7 +579,11 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     }
 
     // Drain: every outstanding command, every kernel, every host copy.
-    hipError_t e1 = hipStreamSynchronize(q->s_copy);
+    hipError_t e1 = hipSuccess;
+    for (int k = 0; k < kMaxCopyStreams; ++k) {
+        hipError_t ek = hipStreamSynchronize(q->s_copy[k]);
+        if (ek != hipSuccess) e1 = ek;
+    }
     hipError_t e2 = hipStreamSynchronize(q->s_compute);
     for (auto &e : q->ring) spin_until_zero(e.pending);
     if (err == KV_OK && (e1 != hipSuccess || e2 != hipSuccess)) {

@@ -243,14 +243,22 @@ def test_decode_attention_16bit_output_and_short_lengths(case):
 
 
 # ------------------------------------------------------------------------------------------ pipeline
-@pytest.mark.parametrize("span_chunks,depth", [(0, 3), (1, 2), (2, 4), (0, 1)])
-def test_pipeline_offload_reload(case, span_chunks, depth):
+# (span_chunks, depth, copy_streams, d2h_mode, h2d_mode)
+PIPE_VARIANTS = [(0, 3, 0, kv.KV_COPY_AUTO, kv.KV_COPY_AUTO),
+                 (1, 2, 1, kv.KV_COPY_MEMCPY, kv.KV_COPY_MEMCPY),
+                 (2, 4, 3, kv.KV_COPY_KERNEL, kv.KV_COPY_KERNEL),
+                 (0, 1, 0, kv.KV_COPY_AUTO, kv.KV_COPY_AUTO),
+                 (0, 8, 4, kv.KV_COPY_MEMCPY, kv.KV_COPY_KERNEL)]
+
+
+@pytest.mark.parametrize("span_chunks,depth,copy_streams,d2h,h2d", PIPE_VARIANTS)
+def test_pipeline_offload_reload(case, span_chunks, depth, copy_streams, d2h, h2d):
     cfg, r = case.cfg, case.ref
     FILL = 0xC3
     region = pinned_bytes(r.region_bytes, FILL)
     arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
     st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena,
-                            depth=depth, span_chunks=span_chunks)
+                            depth=depth, span_chunks=span_chunks, copy_streams=copy_streams, d2h_mode=d2h, h2d_mode=h2d)
     want_region, want_arena = case.expected_host(fill=FILL)
     assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
     assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
@@ -260,7 +268,7 @@ def test_pipeline_offload_reload(case, span_chunks, depth):
     k_new, v_new = case.blank_like_source()
     view = case.make_view(k_new, v_new)
     st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, cfg.n_layers, view, region, arena,
-                            depth=depth, span_chunks=span_chunks)
+                            depth=depth, span_chunks=span_chunks, copy_streams=copy_streams, d2h_mode=d2h, h2d_mode=h2d)
     assert st.max_in_flight <= depth
     _check_restored(case, k_new, v_new, range(cfg.n_layers))
 
