@@ -84,12 +84,59 @@ def cpu_baseline(cfg, W, budget_s: float = 20.0):
             "decode_attn_us_per_layer": round(attn_s / layers * 1e6, 1)}
 
 
+def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps: int):
+    """Resident-KV leg: every kernel of the path launched back to back on whole tensors, rotating over
+    all layers (so each launch touches memory no earlier launch left in the last-level cache), no DMA
+    in flight.  Each kind is bracketed by events on the stream it is launched on (the default stream,
+    which is also PyTorch's current stream here); the figure is the average per launch, gaps included."""
+    L = cfg.n_layers
+    image = int(info.tensor_blocks) * cfg.sector_bytes
+    n_img = max(2, min(2 * L, (1 << 30) // image))        # rotating extent images, about 1 GiB
+    imgs = [torch.empty(image, dtype=torch.uint8, device="cuda") for _ in range(n_img)]
+    max_len = max(lens)
+    ws = torch.empty(kv.kv_decode_attn_workspace(plan, 0, max_len), dtype=torch.uint8, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, n_launches):
+        fn()                                              # warm
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * n_launches)   # microseconds per launch
+
+    def pack_all():
+        i = 0
+        for l in range(L):
+            for kind in (0, 1):
+                kv.kv_offload_pack(plan, l, kind, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[i % n_img])
+                i += 1
+
+    def unpack_all():
+        i = 0
+        for l in range(L):
+            for kind in (0, 1):
+                kv.kv_reload_unpack(plan, l, kind, imgs[i % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
+                i += 1
+
+    def attn_all():
+        for l in range(L):
+            kv.kv_decode_attn(plan, src_view, l, qs[l], outs[l], kv.KV_OUT_F32, 0, ws)
+
+    return {"pack_us": timed(pack_all, 2 * L), "unpack_us": timed(unpack_all, 2 * L), "attn_us": timed(attn_all, L)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="llama8b_32k")
+    ap.add_argument("--leg", choices=["both", "pipeline", "kernels"], default="both",
+                    help="pipeline: the timed steps only; kernels: the resident-KV kernel leg only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--host-workers", type=int, default=0)
     ap.add_argument("--span-chunks", type=int, default=0)
@@ -111,22 +158,22 @@ def main():
     plan = native_plan(cfg, lens)
     info = plan.info
     L = cfg.n_layers
+    n1 = int(info.n_pagecache_layers)
     log(f"[bench] {cfg.name}: L={L} H={cfg.n_kv_heads} Hq={cfg.n_q_heads} D={cfg.head_dim} B={cfg.batch} "
         f"lens={lens if len(set(lens)) > 1 else lens[0]} chunk={cfg.chunk_tokens} depth={cfg.depth} "
-        f"pagecache_layers={info.n_pagecache_layers}")
+        f"pagecache_layers={n1}")
 
     # ---- synthetic KV resident in HBM (seeded N(0,1) in the config's 16-bit dtype)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
     if cfg.layout == W.PAGED:
         table, n_pool = W.block_table(cfg, lens)
         table_dev = table.cuda()
         k = [W.paged_layer(cfg, l, 0, n_pool, "cuda") for l in range(L)]
         v = [W.paged_layer(cfg, l, 1, n_pool, "cuda") for l in range(L)]
-        lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
         mk = lambda kk, vv: kv.paged_view(kk, vv, table_dev, lens, lens_dev)
     else:
         k = [W.bhsd_layer(cfg, l, 0, "cuda") for l in range(L)]
         v = [W.bhsd_layer(cfg, l, 1, "cuda") for l in range(L)]
-        lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
         mk = lambda kk, vv: kv.bhsd_view(kk, vv, lens, lens_dev)
     src_view = mk(k, v)
     k2 = [torch.zeros_like(t) for t in k]
@@ -135,113 +182,135 @@ def main():
     qs = [W.query(cfg, l, "cuda") for l in range(L)]
     outs = [torch.zeros((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda") for _ in range(L)]
 
-    # ---- storage model: pinned LBA region (direct path) + pageable arena (page-cache path)
-    region = torch.empty(max(int(info.region_bytes_needed), 1), dtype=torch.uint8, pin_memory=True)
-    region.zero_()
-    arena = np.zeros(max(int(info.pageable_bytes_needed), 1), dtype=np.uint8)
-    arena[::4096] = 1  # touch every page before timing
-    torch.cuda.synchronize()
-
     payload = 2 * L * int(info.tensor_blocks) * cfg.sector_bytes  # bytes over the link per direction
-
-    def step(timed: bool):
-        a = kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, src_view, region, arena, depth=cfg.depth,
-                               span_chunks=args.span_chunks, host_workers=args.host_workers, time_kernels=timed)
-        b = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD_ATTN, 0, L, dst_view, region, arena, depth=cfg.depth,
-                               q_layers=qs, out_layers=outs, span_chunks=args.span_chunks,
-                               host_workers=args.host_workers, time_kernels=timed)
-        return a, b
-
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    stats = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        stats.append(step(True))
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    value = 2 * payload * args.steps / elapsed / 1e9
-
-    # round trip must be exact (cheap on-device check of the timed work's result)
-    for l in (0, L - 1):
-        assert torch.equal(k[l].view(torch.int16), k2[l].view(torch.int16)), "reload differs from source"
-        assert torch.equal(v[l].view(torch.int16), v2[l].view(torch.int16)), "reload differs from source"
-
-    off_s = sum(a.wall_s for a, _ in stats) / args.steps
-    rel_s = sum(b.wall_s for _, b in stats) / args.steps
-
-    def kstat(kind, which):
-        ms = sum(s[which].kernel_ms[kind] for s in stats)
-        n = sum(s[which].kernel_launches[kind] for s in stats)
-        return (ms / n * 1e3 if n else 0.0), n  # microseconds per launch
-
     tensor_payload = int(info.tensor_payload_bytes)
     tensor_image = int(info.tensor_blocks) * cfg.sector_bytes
-    pack_us, pack_n = kstat(kv.KV_KERNEL_PACK, 0)
-    unpack_us, unpack_n = kstat(kv.KV_KERNEL_UNPACK, 1)
-    attn_us, attn_n = kstat(kv.KV_KERNEL_ATTN_PARTIAL, 1)
-    launches_per_tensor_pack = pack_n / (2 * L * args.steps)
-    launches_per_tensor_unpack = unpack_n / (2 * L * args.steps)
-    rooflines = []
-    for name, us, per_launch in (
-            ("kv_layout_kernel<pack>", pack_us, (tensor_payload + tensor_image) / launches_per_tensor_pack),
-            ("kv_layout_kernel<unpack>", unpack_us, 2 * tensor_payload / launches_per_tensor_unpack),
-            ("kv_attn_partial_kernel+combine", attn_us, 2 * tensor_payload)):
-        ach = per_launch / (us * 1e-6) / 1e9 if us > 0 else 0.0
-        rooflines.append({"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                          "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
-                          "us_per_launch": round(us, 2), "bytes_per_launch": int(per_launch)})
-    totals = [pack_us * pack_n, unpack_us * unpack_n, attn_us * attn_n]
-    dominant = rooflines[max(range(3), key=lambda i: totals[i])]
-
-    link = measure_link(torch, min(payload, 2 << 30))
-    off_gbps = payload / off_s / 1e9
-    rel_gbps = payload / rel_s / 1e9
-
-    # per-path throughput (outside the timed region): page-cache-path layers and direct-path layers alone
-    n1 = int(info.n_pagecache_layers)
-    per_path = {}
-    for label, lo, hi in (("pagecache", 0, n1), ("direct", n1, L)):
-        if hi > lo:
-            a = kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, lo, hi, src_view, region, arena, depth=cfg.depth,
-                                   span_chunks=args.span_chunks, host_workers=args.host_workers)
-            b = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD, lo, hi, dst_view, region, arena, depth=cfg.depth,
-                                   span_chunks=args.span_chunks, host_workers=args.host_workers)
-            nb = (a.bytes_direct + a.bytes_pagecache)
-            per_path[label] = {"offload_GBps": round(nb / a.wall_s / 1e9, 2), "reload_GBps": round(nb / b.wall_s / 1e9, 2),
-                               "offload_frac_of_link": round(nb / a.wall_s / 1e9 / link["d2h"], 3),
-                               "reload_frac_of_link": round(nb / b.wall_s / 1e9 / link["h2d"], 3)}
-
-    # overlap: how much of everything that is not link time was hidden behind the link
-    kern_s = (pack_us * pack_n + unpack_us * unpack_n + attn_us * attn_n) * 1e-6 / args.steps
-    t_link = payload / (link["d2h"] * 1e9) + payload / (link["h2d"] * 1e9)
-    t_pipe = off_s + rel_s
-    overlap = None
-    if n1 == 0 and kern_s > 0:
-        overlap = round(max(0.0, min(1.0, (t_link + kern_s - t_pipe) / kern_s)), 3)
-
     res = {
         "metric": "KV offload+reload GB/s and decode-attn us/layer, 8B-shape KV at 32K ctx",
-        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} layers, {cfg.n_kv_heads} KV heads, {cfg.n_q_heads} query heads, "
                                f"head_dim {cfg.head_dim}, batch {cfg.batch}, context {max(lens)}, {cfg.dtype} K/V, "
                                f"{cfg.sector_bytes} B sectors",
                    "chunk_tokens": cfg.chunk_tokens, "depth": cfg.depth, "pagecache_layers": n1,
-                   "span_chunks": args.span_chunks, "layout": cfg.layout, "extent_mode": cfg.extent_mode},
-        "offload_GBps": round(off_gbps, 2), "reload_attn_GBps": round(rel_gbps, 2),
-        "decode_attn_us_per_layer": round(attn_us, 2),
-        "host_link": {"h2d_GBps": round(link["h2d"], 2), "d2h_GBps": round(link["d2h"], 2),
-                      "offload_frac": round(off_gbps / link["d2h"], 3), "reload_frac": round(rel_gbps / link["h2d"], 3),
-                      "how": "back-to-back pinned 64 MiB copies, no kernels"},
-        "per_path": per_path,
-        "overlap_fraction": overlap,
-        "roofline": {k2_: dominant[k2_] for k2_ in ("bound", "achieved", "peak", "unit", "frac", "traffic")} | {"kernel": dominant["kernel"]},
-        "rooflines": rooflines,
+                   "span_chunks": args.span_chunks, "layout": cfg.layout, "extent_mode": cfg.extent_mode,
+                   "leg": args.leg},
     }
+
+    def roof(name, us, per_launch, where):
+        ach = per_launch / (us * 1e-6) / 1e9 if us > 0 else 0.0
+        return {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "us_per_launch": round(us, 2),
+                "bytes_per_launch": int(per_launch), "where": where}
+
+    if args.leg in ("both", "pipeline"):
+        # ---- storage model: pinned LBA region (direct path) + pageable arena (page-cache path)
+        region = torch.empty(max(int(info.region_bytes_needed), 1), dtype=torch.uint8, pin_memory=True)
+        region.zero_()
+        arena = np.zeros(max(int(info.pageable_bytes_needed), 1), dtype=np.uint8)
+        arena[::4096] = 1  # touch every page before timing
+        torch.cuda.synchronize()
+
+        def step(timed: bool):
+            a = kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, src_view, region, arena, depth=cfg.depth,
+                                   span_chunks=args.span_chunks, host_workers=args.host_workers, time_kernels=timed)
+            b = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD_ATTN, 0, L, dst_view, region, arena, depth=cfg.depth,
+                                   q_layers=qs, out_layers=outs, span_chunks=args.span_chunks,
+                                   host_workers=args.host_workers, time_kernels=timed)
+            return a, b
+
+        for _ in range(args.warmup):
+            step(False)
+        torch.cuda.synchronize()
+        stats = []
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            stats.append(step(True))
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        res["ms_per_step"] = round(elapsed / args.steps * 1e3, 3)
+        res["value"] = round(2 * payload * args.steps / elapsed / 1e9, 3)
+
+        # the timed work's result: the reloaded cache must equal the source bit for bit
+        for l in (0, L - 1):
+            assert torch.equal(k[l].view(torch.int16), k2[l].view(torch.int16)), "reload differs from source"
+            assert torch.equal(v[l].view(torch.int16), v2[l].view(torch.int16)), "reload differs from source"
+
+        off_s = sum(a.wall_s for a, _ in stats) / args.steps
+        rel_s = sum(b.wall_s for _, b in stats) / args.steps
+
+        def kstat(kind, which):
+            ms = sum(s[which].kernel_ms[kind] for s in stats)
+            n = sum(s[which].kernel_launches[kind] for s in stats)
+            return (ms / n * 1e3 if n else 0.0), n  # microseconds per launch
+
+        pack_us, pack_n = kstat(kv.KV_KERNEL_PACK, 0)
+        unpack_us, unpack_n = kstat(kv.KV_KERNEL_UNPACK, 1)
+        attn_us, attn_n = kstat(kv.KV_KERNEL_ATTN_PARTIAL, 1)
+        per_t_pack = pack_n / (2 * L * args.steps)
+        per_t_unpack = unpack_n / (2 * L * args.steps)
+        where = "inside the pipeline steps (DMA in flight, GPU otherwise idle)"
+        res["rooflines_in_pipeline"] = [
+            roof("kv_layout_kernel<pack>", pack_us, (tensor_payload + tensor_image) / per_t_pack, where),
+            roof("kv_layout_kernel<unpack>", unpack_us, 2 * tensor_payload / per_t_unpack, where),
+            roof("kv_attn_partial_kernel+kv_attn_combine_kernel", attn_us, 2 * tensor_payload, where)]
+
+        link = measure_link(torch, min(payload, 2 << 30))
+        off_gbps = payload / off_s / 1e9
+        rel_gbps = payload / rel_s / 1e9
+        res["offload_GBps"] = round(off_gbps, 2)
+        res["reload_attn_GBps"] = round(rel_gbps, 2)
+        res["host_link"] = {"h2d_GBps": round(link["h2d"], 2), "d2h_GBps": round(link["d2h"], 2),
+                            "offload_frac": round(off_gbps / link["d2h"], 3),
+                            "reload_frac": round(rel_gbps / link["h2d"], 3),
+                            "how": "back-to-back pinned 64 MiB copies, no kernels, same run"}
+
+        # per-path throughput (outside the timed region): page-cache-path layers and direct-path layers alone
+        per_path = {}
+        for label, lo, hi in (("pagecache", 0, n1), ("direct", n1, L)):
+            if hi > lo:
+                a = kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, lo, hi, src_view, region, arena, depth=cfg.depth,
+                                       span_chunks=args.span_chunks, host_workers=args.host_workers)
+                b = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD, lo, hi, dst_view, region, arena, depth=cfg.depth,
+                                       span_chunks=args.span_chunks, host_workers=args.host_workers)
+                nb = a.bytes_direct + a.bytes_pagecache
+                per_path[label] = {"offload_GBps": round(nb / a.wall_s / 1e9, 2),
+                                   "reload_GBps": round(nb / b.wall_s / 1e9, 2),
+                                   "offload_frac_of_link": round(nb / a.wall_s / 1e9 / link["d2h"], 3),
+                                   "reload_frac_of_link": round(nb / b.wall_s / 1e9 / link["h2d"], 3)}
+        res["per_path"] = per_path
+
+        # overlap fraction = (T_serial - T_pipe) / (T_serial - T_link): T_serial is one step with every
+        # stage run to completion before the next starts, T_link the same bytes at the measured link rate
+        sa = kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, src_view, region, arena, depth=1, serialize=True,
+                                span_chunks=args.span_chunks, host_workers=args.host_workers)
+        sb = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD_ATTN, 0, L, dst_view, region, arena, depth=1, serialize=True,
+                                q_layers=qs, out_layers=outs, span_chunks=args.span_chunks,
+                                host_workers=args.host_workers)
+        t_serial = sa.wall_s + sb.wall_s
+        t_link = payload / (link["d2h"] * 1e9) + payload / (link["h2d"] * 1e9)
+        t_pipe = off_s + rel_s
+        res["overlap"] = {"serial_s": round(t_serial, 5), "pipeline_s": round(t_pipe, 5), "link_s": round(t_link, 5),
+                          "fraction": round((t_serial - t_pipe) / (t_serial - t_link), 3) if t_serial > t_link else None}
+        res["decode_attn_us_per_layer_in_pipeline"] = round(attn_us, 2)
+        del region, arena
+
+    if args.leg in ("both", "kernels"):
+        kl = kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps=max(3, args.steps))
+        where = "resident-KV leg: whole-tensor launches back to back, rotating over all layers"
+        rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], tensor_payload + tensor_image, where),
+              roof("kv_layout_kernel<unpack>", kl["unpack_us"], 2 * tensor_payload, where),
+              roof("kv_attn_partial_kernel+kv_attn_combine_kernel", kl["attn_us"], 2 * tensor_payload, where)]
+        res["rooflines"] = rl
+        res["decode_attn_us_per_layer"] = round(kl["attn_us"], 2)
+        # the dominant kernel of a step: the one with the most GPU time over its launches
+        tot = [kl["pack_us"] * 2 * L, kl["unpack_us"] * 2 * L, kl["attn_us"] * L]
+        dom = rl[max(range(3), key=lambda i: tot[i])]
+        res["roofline"] = {key: dom[key] for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "where")}
+    else:
+        dom = max(res["rooflines_in_pipeline"], key=lambda r: r["us_per_launch"])
+        res["roofline"] = {key: dom[key] for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "where")}
 
     if not args.no_cpu_baseline and cfg.layout == W.BHSD:
         log("[bench] timing the CPU checker on a bounded sample ...")

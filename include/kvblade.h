@@ -148,6 +148,8 @@ typedef struct kv_attn_args {
 #define KV_KERNEL_ATTN_COMBINE 3
 
 #define KV_PIPE_TIME_KERNELS 1u /* bracket every kernel with hipEvents and fill kernel_ms */
+#define KV_PIPE_SERIALIZE 2u    /* run every stage (kernel, chunk transfer, host copy) to completion before
+                                   the next starts: the no-overlap reference for the overlap fraction */
 
 #define KV_COPY_AUTO 0   /* D2H: copy kernel; H2D: hipMemcpyAsync (the faster of the two, as measured) */
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
@@ -171,7 +173,8 @@ typedef struct kv_pipe_stats {
     uint32_t n_spans;         /* staging slots filled */
     uint32_t max_in_flight;   /* largest number of chunk commands outstanding at once */
     uint32_t kernel_launches[4];
-    float kernel_ms[4];       /* summed event-bracketed time per kernel kind (KV_PIPE_TIME_KERNELS) */
+    float kernel_ms[4];       /* summed event-bracketed time per kernel kind (KV_PIPE_TIME_KERNELS); the
+                                 attention pair is bracketed together and reported under ATTN_PARTIAL */
 } kv_pipe_stats_t;
 
 /* ------------------------------------------------------------------------------------------ */

@@ -56,7 +56,7 @@ __device__ __forceinline__ void st(u32x4 *p, u32x4 v)
 }
 
 // PACK: source -> image.  !PACK: image -> source.  U = token rows in flight per thread.
-template <bool PACK, bool PAGED, int U>
+template <bool PACK, bool PAGED, int U, bool NTL, bool NTS>
 __global__ void __launch_bounds__(kThreads)
 kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, int rx_log2, int tpb)
 {
@@ -112,7 +112,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const unsigned long long i = sg.img_off + (unsigned long long)(t0 + u * TY) * rowv + r;
-                if (ok[u]) v[u] = PACK ? ld<true>(s.base + a[u]) : ld<true>(img + i);
+                if (ok[u]) v[u] = PACK ? ld<NTL>(s.base + a[u]) : ld<NTL>(img + i);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -121,9 +121,9 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
                     // a skipped block id still owns its bytes of the image: they read as zero
                     const bool in = (t0 + u * TY) < t_end;
                     const u32x4 z = {0u, 0u, 0u, 0u};
-                    if (in) st<true>(img + i, ok[u] ? v[u] : z);
+                    if (in) st<NTS>(img + i, ok[u] ? v[u] : z);
                 } else if (ok[u]) {
-                    st<true>(s.base + a[u], v[u]);
+                    st<NTS>(s.base + a[u], v[u]);
                 }
             }
         }
@@ -190,7 +190,33 @@ SrcDesc make_src(const kv_plan *p, const kv_view_t *v, int layer, int kind)
     return s;
 }
 
+// Launch shape, settable for measurement sweeps (defaults are the measured best on MI355X).
 int g_tile_bytes = 64 * 1024;  // extent bytes one workgroup moves
+int g_unroll = 4;              // token rows in flight per thread: 2, 4 or 8
+bool g_nt_load = true, g_nt_store = true;
+
+template <bool PACK, bool PAGED, int U>
+void launch_nt(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv, int rx_log2,
+               int tpb)
+{
+    u32x4 *im = (u32x4 *)img;
+    if (g_nt_load) {
+        if (g_nt_store) hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, true, true>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb);
+        else hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, true, false>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb);
+    } else {
+        if (g_nt_store) hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, false, true>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb);
+        else hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, false, false>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb);
+    }
+}
+
+template <bool PACK, bool PAGED>
+void launch_u(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv, int rx_log2,
+              int tpb)
+{
+    if (g_unroll == 8) launch_nt<PACK, PAGED, 8>(grid, stream, s, img, tab, rowv, rx_log2, tpb);
+    else if (g_unroll == 2) launch_nt<PACK, PAGED, 2>(grid, stream, s, img, tab, rowv, rx_log2, tpb);
+    else launch_nt<PACK, PAGED, 4>(grid, stream, s, img, tab, rowv, rx_log2, tpb);
+}
 
 template <bool PACK>
 int launch(const kv_plan *p, const kv_view_t *v, int layer, int kind, const Seg *segs, int nseg, void *img,
@@ -200,7 +226,7 @@ int launch(const kv_plan *p, const kv_view_t *v, int layer, int kind, const Seg 
     int rx_log2 = 0;
     while ((1 << rx_log2) < rowv && rx_log2 < 8) ++rx_log2;
     const int TY = kThreads >> rx_log2;
-    constexpr int U = 4;
+    const int U = g_unroll == 8 ? 8 : (g_unroll == 2 ? 2 : 4);
     int tpb = (int)std::max<long long>(1, g_tile_bytes / (long long)p->row_bytes);
     tpb = (tpb + TY * U - 1) / (TY * U) * (TY * U);
     const SrcDesc s = make_src(p, v, layer, kind);
@@ -215,12 +241,8 @@ int launch(const kv_plan *p, const kv_view_t *v, int layer, int kind, const Seg 
             max_tok = std::max(max_tok, segs[g0 + i].ntok);
         }
         dim3 grid((unsigned)std::max(1, (max_tok + tpb - 1) / tpb), (unsigned)n);
-        if (paged)
-            hipLaunchKernelGGL((kv_layout_kernel<PACK, true, U>), grid, dim3(kThreads), 0, stream, s, (u32x4 *)img,
-                               tab, rowv, rx_log2, tpb);
-        else
-            hipLaunchKernelGGL((kv_layout_kernel<PACK, false, U>), grid, dim3(kThreads), 0, stream, s, (u32x4 *)img,
-                               tab, rowv, rx_log2, tpb);
+        if (paged) launch_u<PACK, true>(grid, stream, s, img, tab, rowv, rx_log2, tpb);
+        else launch_u<PACK, false>(grid, stream, s, img, tab, rowv, rx_log2, tpb);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
     }
@@ -294,7 +316,14 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
 }  // namespace
 
 namespace kvb {
-void set_layout_tile_bytes(int bytes) { if (bytes >= 1024) g_tile_bytes = bytes; }
+// Measurement hook (not part of the C ABI): launch shape of the pack / unpack kernels.
+void set_layout_tuning(int tile_bytes, int unroll, bool nt_load, bool nt_store)
+{
+    if (tile_bytes >= 1024) g_tile_bytes = tile_bytes;
+    if (unroll == 2 || unroll == 4 || unroll == 8) g_unroll = unroll;
+    g_nt_load = nt_load;
+    g_nt_store = nt_store;
+}
 }
 
 extern "C" int kv_offload_pack(const kv_plan_t *plan, int layer, int kind, const kv_view_t *src, int seq, int tok0,

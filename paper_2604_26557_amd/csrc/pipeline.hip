@@ -296,6 +296,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const int span_chunks = opts ? opts->span_chunks : 0;
     const int n_workers = opts && opts->host_workers > 0 ? opts->host_workers : 8;
     const bool time_kernels = opts && (opts->flags & KV_PIPE_TIME_KERNELS);
+    const bool serialize = opts && (opts->flags & KV_PIPE_SERIALIZE);
     if (span_chunks < 0 || n_workers > 64) return KV_EINVAL;
     const bool offload_dir = dir == KV_DIR_OFFLOAD;
     int ns = opts ? opts->copy_streams : 0;
@@ -460,7 +461,9 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (!by_kernel)
             return hipMemcpyAsync(dst, src, bytes, to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, st);
         const size_t nvec = bytes / 16;
-        const unsigned blocks = (unsigned)std::min<size_t>(256, std::max<size_t>(1, nvec / (256 * 4)));
+        // 32 workgroups saturate the link (measured); a small grid also keeps the compute units whose
+        // store path backs up behind PCIe writes few, so the concurrent pack kernel is disturbed less
+        const unsigned blocks = (unsigned)std::min<size_t>(32, std::max<size_t>(1, nvec / (256 * 4)));
         hipLaunchKernelGGL(kv_chunk_copy_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4 *)src, (u32x4 *)dst, nvec);
         return hipGetLastError();
     };
@@ -484,6 +487,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 if (err != KV_OK) break;
                 if (stats) { stats->kernel_launches[KV_KERNEL_PACK]++; stats->n_spans++; }
                 KV_HIP_BRK(hipEventRecord(q->ev_ready[slot], q->s_compute));
+                if (serialize) KV_HIP_BRK(hipStreamSynchronize(q->s_compute));
                 used = 0;
             }
             if ((err = acquire(c)) != KV_OK) break;
@@ -503,6 +507,10 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 fan_out(c, host_ptr(ch), bounce_ptr(c), ch.bytes, e.ev);
             }
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(c + 1 - n_waited));
+            if (serialize) {  // every stage to completion before the next starts
+                while (n_waited <= c && err == KV_OK) { err = wait_complete(n_waited); ++n_waited; }
+                if (err != KV_OK) break;
+            }
             if (ch.last) {
                 for (int k = 0; k < ns && err == KV_OK; ++k)
                     if (used >> k & 1) KV_HIP_SET(hipEventRecord(q->ev_done[slot * kMaxCopyStreams + k], q->s_copy[k]));
@@ -516,7 +524,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     } else {
         // Reload.  Page-cache-path chunks are started (arena -> bounce memcpy) a few commands ahead of
         // their H2D issue; a direct chunk starts when it is issued.
-        const size_t look = std::max<size_t>(1, (size_t)depth / 2);
+        const size_t look = serialize ? 1 : std::max<size_t>(1, (size_t)depth / 2);
         size_t cs = 0;  // next chunk to start
         for (size_t ci = 0; ci < N && err == KV_OK; ++ci) {
             while (cs < N && err == KV_OK) {
@@ -549,6 +557,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st));
             }
             KV_HIP_BRK(hipEventRecord(e.ev, st));
+            if (serialize) KV_HIP_BRK(hipEventSynchronize(e.ev));
             if (stats) {
                 stats->n_chunks++;
                 (sp.path == KV_PATH_DIRECT ? stats->bytes_direct : stats->bytes_pagecache) += ch.bytes;
@@ -574,6 +583,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                     if (err != KV_OK) break;
                     if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
                 }
+                if (serialize) KV_HIP_BRK(hipStreamSynchronize(q->s_compute));
             }
         }
     }

@@ -1,0 +1,92 @@
+"""GPU parity at the full sizes of the evaluation configs, in the launch configuration bench.py times
+(whole-tensor kernel spans, the config's chunk size and depth, default copy engines).
+
+The CPU checker cannot do a whole cache element by element in test time, so:
+  * sampled tensors (first / last of each path) are compared byte for byte with the checker's extent,
+  * every layer is checked by a property that holds at any size: reload(offload(x)) == x bit for bit,
+    and bytes outside all extents (the hole below lba_start) keep their fill pattern,
+  * decode attention is compared with the fp64 checker on sampled layers.
+Inputs are generated on the GPU from the seeded generator; the checker sees copies of the same bits.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_oracle as o
+from paper_2604_26557_amd import binding as kv
+from paper_2604_26557_amd import workloads as W
+from kvcase import Case, bits, pinned_bytes
+
+pytestmark = pytest.mark.gpu
+
+ATTN_ATOL = 2e-3
+ATTN_REL_OF_MAX = 1e-2
+FILL = 0xC3
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4], ids=lambda i: W.CONFIGS[i].name)
+def test_full_size_offload_reload_attention(idx):
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[idx]
+    print(f"full-size case {cfg.name} seed {cfg.seed}", flush=True)
+    case = Case(cfg, "cuda", keep_cpu=False)
+    r, L = case.ref, cfg.n_layers
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, L, case.view, region, arena, depth=cfg.depth)
+    assert st.max_in_flight <= cfg.depth
+    assert st.bytes_direct == r.direct_blocks * r.lba_size and st.bytes_pagecache == r.pageable_bytes
+
+    # sampled tensors against the checker, byte for byte (payload and zero pad)
+    n1 = r.n1
+    sample = {(n1, 0), (L - 1, 1)} | ({(0, 0), (n1 - 1, 1)} if n1 > 0 else set())
+    region_np = region.numpy()
+    ext_bytes = r.n_blocks_tensor * r.lba_size
+    for layer, kind in sorted(sample):
+        t_cpu = (case.k if kind == 0 else case.v)[layer].cpu()
+        want = case.expected_extent(layer, kind, t_cpu)
+        n = 2 * layer + kind
+        buf = region_np if r.path[n] == 0 else arena
+        off = r.ext_byte_off(n)
+        assert np.array_equal(buf[off:off + ext_bytes], want), (layer, kind)
+    # the hole below the first LBA is never written
+    assert (region_np[:cfg.lba_start * cfg.sector_bytes] == FILL).all()
+
+    # reload + attention; every layer must come back bit for bit
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    qd = [W.query(cfg, l, "cuda") for l in range(L)]
+    outs = [torch.full((cfg.batch, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+            for _ in range(L)]
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, L, view, region, arena, depth=cfg.depth,
+                            q_layers=qd, out_layers=outs)
+    assert st.max_in_flight <= cfg.depth
+    if case.paged:
+        # slots past a sequence's length are not part of the cache: compare valid tokens only
+        bt = cfg.block_tokens
+        valid = torch.zeros((case.n_pool, bt), dtype=torch.bool)
+        table = case.table_cpu
+        for b, n in enumerate(case.lens):
+            nb = -(-n // bt)
+            valid[table[b, :nb].long()] = True
+            if n % bt:
+                valid[table[b, nb - 1].long(), n % bt:] = False
+        m = valid.cuda()[:, None, :, None]
+        for l in range(L):
+            for a, b_ in ((case.k[l], k_new[l]), (case.v[l], v_new[l])):
+                assert torch.equal(torch.where(m, a.view(torch.int16), 0), torch.where(m, b_.view(torch.int16), 0)), l
+    else:
+        for l in range(L):
+            assert torch.equal(case.k[l].view(torch.int16), k_new[l].view(torch.int16)), l
+            assert torch.equal(case.v[l].view(torch.int16), v_new[l].view(torch.int16)), l
+
+    for layer in sorted({0, L - 1}):
+        K, V, q = case.k[layer].cpu(), case.v[layer].cpu(), qd[layer].cpu()
+        want = o.attention(case.source(K), o.u16(K), o.u16(V), o.u16(q), cfg.dtype == W.BF16, case.lens, cfg.n_q_heads)
+        got = outs[layer].double().cpu().numpy()
+        err, scale = np.abs(got - want).max(), np.abs(want).max()
+        print(f"  layer {layer}: attention max abs err {err:.3e}, reference max {scale:.3e}", flush=True)
+        assert err <= ATTN_ATOL and err <= ATTN_REL_OF_MAX * scale, (layer, err, scale)
+    for l in range(L):
+        assert torch.isfinite(outs[l]).all()
