@@ -126,7 +126,14 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         for l in range(L):
             kv.kv_decode_attn(plan, src_view, l, qs[l], outs[l], kv.KV_OUT_F32, 0, ws)
 
-    return {"pack_us": timed(pack_all, 2 * L), "unpack_us": timed(unpack_all, 2 * L), "attn_us": timed(attn_all, L)}
+    def copy_ref():
+        # plain device-to-device copies of one extent image each: the known-size reference that hardware
+        # byte counters of the kernels above are scaled by
+        for i in range(8):
+            imgs[(i + 1) % n_img].copy_(imgs[i % n_img])
+
+    return {"pack_us": timed(pack_all, 2 * L), "unpack_us": timed(unpack_all, 2 * L), "attn_us": timed(attn_all, L),
+            "copy_ref_us": timed(copy_ref, 8), "copy_ref_bytes": image}
 
 
 def main():

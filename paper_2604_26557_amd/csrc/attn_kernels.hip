@@ -1,12 +1,19 @@
 // Split-K decode attention over resident KV (Sec. II-A: the query's similarity with the keys weights
 // the values):  out[b,hq,:] = softmax_j(q[b,hq,:].K[b,h,j,:] / sqrt(D)) V[b,h,j,:],  h = hq / G.
 //
-// Partial kernel, grid (split, query-head group, b), 4 wavefronts per workgroup.  A K or V row of D
-// 16-bit elements is held by D/8 lanes (16 bytes each), so one wavefront load covers 64/(D/8)
-// consecutive rows = 1 KiB of contiguous memory.  Each lane group keeps its own running (m, l, acc)
-// in fp32 for the GT query heads that share the kv head (K and V are read once for all of them);
-// groups, then wavefronts, are merged at the end and one fp32 partial per (b, hq, split) is written.
-// The combine kernel merges the splits.  The path is HBM-bound (G flop per byte).
+// Partial kernel, grid (split, query-head group, b), 4 wavefronts per workgroup, each walking 16-token
+// tiles of its split.
+//  * q K^T on the matrix cores: one v_mfma_f32_16x16x32 per 32-wide slice of D with the K tile as the
+//    16 x 32 A operand (lane = token row, 16 contiguous bytes of it) and the query heads of the group,
+//    repeated across the 16 columns, as the B operand.  A 16-byte global load is exactly one operand
+//    register set, so K never passes through LDS, and no cross-lane reduction over D is needed.
+//  * The 16 x 16 fp32 result leaves lane (column n, row group tg) with the scores of tokens 4tg..4tg+3
+//    for query head n mod GT.  Each lane runs the running softmax (m, l) of its own (head, row group)
+//    in fp32; probabilities and rescale factors reach the other heads' lanes by quad broadcasts (DPP).
+//  * P V stays on the vector ALU: the 16 lanes of a row group hold the V rows of their own 4 tokens
+//    (16 bytes per lane), so acc[g][d] += p[g][token] * V[token][d] needs no transpose of V.
+// Row groups, then wavefronts, are merged at the end and one fp32 partial per (b, hq, split) is
+// written; the combine kernel merges the splits.  HBM-bound (G flop per byte).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -19,10 +26,15 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kR = 4;                 // rows in flight per lane group
-constexpr float kEmptyMax = -1.0e30f; // running maximum of a group that has seen no token
+constexpr int kTile = 16;             // tokens per MFMA tile
+constexpr int tiles_per_iter(int D) { return D >= 256 ? 1 : (D == 128 ? 2 : 4); }
+constexpr float kEmptyMax = -1.0e30f; // running maximum of a row group that has seen no token
 
 struct AttnParams {
     const u32x4 *K, *V;    // attention-side buffers of the layer
@@ -56,6 +68,24 @@ __device__ __forceinline__ void unpack8(u32x4 v, float f[8])
     }
 }
 
+// Value of quad lane Q (0..3) in every lane of the quad.
+template <int Q>
+__device__ __forceinline__ float quad_bcast(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), Q * 0x55, 0xf, 0xf, false));
+}
+template <int GT>
+__device__ __forceinline__ float head_bcast(float x, int g)
+{
+    if (GT == 1) return x;
+    switch (g) {
+    case 0: return quad_bcast<0>(x);
+    case 1: return quad_bcast<1>(x);
+    case 2: return quad_bcast<2>(x);
+    default: return quad_bcast<3>(x);
+    }
+}
+
 // Merge the running softmax state of another lane / wavefront into this one.
 template <int N>
 __device__ __forceinline__ void merge(float &m, float &l, float acc[N], float m2, float l2, const float acc2[N])
@@ -68,133 +98,182 @@ __device__ __forceinline__ void merge(float &m, float &l, float acc[N], float m2
     m = M;
 }
 
-template <int LPR, int GT, bool BF16, bool PAGED>
+template <bool BF16>
+__device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c)
+{
+    if (BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+template <int D, int GT, bool BF16, bool PAGED>
 __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
 {
-    constexpr int RPW = 64 / LPR;  // rows per wavefront load
-    constexpr int D = LPR * 8;
+    constexpr int NJ = D / 32;               // MFMA slices along D
+    constexpr int DV = D / 8;                // 16-byte vectors per row
+    constexpr int LPRV = DV < 16 ? DV : 16;  // lanes holding one V row inside a 16-lane row group
+    constexpr int TPL = 16 / LPRV;           // V rows one row group covers per load (1, or 2 when D = 64)
+    constexpr int NV = DV / LPRV;            // vectors per lane per V row (1, or 2 when D = 256)
+    constexpr int NU = 4 / TPL;              // V loads (per vector) for the 4 tokens of a row group
+    constexpr int AE = 8 * NV;               // accumulator elements per head per lane
+    constexpr int TI = tiles_per_iter(D);    // tiles whose loads are issued together (16 KiB in flight per wavefront)
+
     const int split = blockIdx.x, hq0 = blockIdx.y * GT, b = blockIdx.z;
     const int h = hq0 / p.G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int lr = lane % LPR;  // position inside the row (16-byte vector index)
-    const int rg = lane / LPR;  // lane group = which of the RPW rows of a load
+    const int n = lane & 15;    // MFMA column; also the K row this lane loads
+    const int tg = lane >> 4;   // row group: owns tokens 4tg..4tg+3 of a tile; also the D sub-slice of the operands
+    const int g_own = n % GT;
+    const int lr = n % LPRV, half = n / LPRV;
 
     const int len = min(p.seq_lens[b], p.max_len);
     const int t_begin = min(len, split * p.split_tokens);
     const int t_end = min(len, t_begin + p.split_tokens);
 
-    // q for the GT heads, pre-scaled so that scores are in log2 units.
-    float qf[GT][8];
+    // B operand: column n carries query head n mod GT; this lane holds elements 32j + 8tg .. +7 of it.
+    u32x4 qv[NJ];
 #pragma unroll
-    for (int g = 0; g < GT; ++g) {
-        const u32x4 qv = p.q[((long long)b * p.Hq + hq0 + g) * LPR + lr];
-        unpack8<BF16>(qv, qf[g]);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) qf[g][i] *= p.scale_log2e;
-    }
+    for (int j = 0; j < NJ; ++j) qv[j] = p.q[((long long)b * p.Hq + hq0 + g_own) * DV + 4 * j + tg];
 
-    float m[GT], l[GT], acc[GT][8];
+    float m_own = kEmptyMax, l_own = 0.f;
+    float acc[GT][AE];
 #pragma unroll
-    for (int g = 0; g < GT; ++g) {
-        m[g] = kEmptyMax;
-        l[g] = 0.f;
+    for (int g = 0; g < GT; ++g)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
-    }
+        for (int e = 0; e < AE; ++e) acc[g][e] = 0.f;
 
-    const long long head_off = PAGED ? 0 : (long long)b * p.sb + (long long)h * p.sh + lr;
+    const long long head_off = PAGED ? 0 : (long long)b * p.sb + (long long)h * p.sh;
     const int *tbl = PAGED ? p.table + (long long)b * p.max_blocks : nullptr;
-    constexpr int kRowsPerIter = kWaves * RPW * kR;
+    // vector index of the first element of token row `row`; ok = false for a block id outside the pool
+    auto row_base = [&](int row, bool &ok) -> long long {
+        if (PAGED) {
+            const int j = p.bt_shift >= 0 ? (row >> p.bt_shift) : (row / p.bt);
+            const int slot = row - j * p.bt;
+            int blk = tbl[j];
+            if ((unsigned)blk >= (unsigned)p.n_pool) { blk = 0; ok = false; }
+            return (((long long)blk * p.H + h) * p.bt + slot) * DV;
+        }
+        return head_off + (long long)row * p.ss;
+    };
 
-    for (int t0 = t_begin; t0 < t_end; t0 += kRowsPerIter) {
-        u32x4 kv[kR], vv[kR];
-        bool ok[kR];
+    for (int Tw = t_begin + kTile * TI * wave; Tw < t_end; Tw += kTile * TI * kWaves) {
+        // ---- loads of TI adjacent tiles: K tile in A-operand order, V rows of this row group's tokens
+        u32x4 kvec[TI][NJ];
+        u32x4 vvec[TI][NU][NV];
+        bool tok_ok[TI][4];
 #pragma unroll
-        for (int u = 0; u < kR; ++u) {
-            const int row = t0 + (u * kWaves + wave) * RPW + rg;
-            ok[u] = row < t_end;
-            const int rr = ok[u] ? row : t_begin;  // a valid row; its score is masked below
-            long long a;
-            if (PAGED) {
-                const int j = p.bt_shift >= 0 ? (rr >> p.bt_shift) : (rr / p.bt);
-                const int slot = rr - j * p.bt;
-                int blk = tbl[j];
-                if ((unsigned)blk >= (unsigned)p.n_pool) { blk = 0; ok[u] = false; }
-                a = (((long long)blk * p.H + h) * p.bt + slot) * LPR + lr;
-            } else {
-                a = head_off + (long long)rr * p.ss;
+        for (int ti = 0; ti < TI; ++ti) {
+            const int T0 = Tw + kTile * ti;
+            bool k_ok = true;
+            const int krow = (T0 + n < t_end) ? T0 + n : t_begin;  // rows past the end re-read a valid row; masked below
+            const long long kb = row_base(krow, k_ok);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) kvec[ti][j] = p.K[kb + 4 * j + tg];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) tok_ok[ti][i] = (T0 + 4 * tg + i) < t_end;
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int i = u * TPL + half;
+                const int tok = T0 + 4 * tg + i;
+                bool ok = true;
+                const long long vb = row_base(tok < t_end ? tok : t_begin, ok);
+#pragma unroll
+                for (int w = 0; w < NV; ++w) vvec[ti][u][w] = p.V[vb + lr + w * LPRV];
+                // a token whose block id is outside the pool is not attended; every lane of the row
+                // group must agree, so the flag is taken per token, not per lane
+                if (PAGED && TPL == 1) tok_ok[ti][u] = tok_ok[ti][u] && ok;
             }
-            kv[u] = p.K[a];
-            vv[u] = p.V[a];
+            if (PAGED && TPL == 2) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    bool ok = true;
+                    const int tok = T0 + 4 * tg + i;
+                    (void)row_base(tok < t_end ? tok : t_begin, ok);
+                    tok_ok[ti][i] = tok_ok[ti][i] && ok;
+                }
+            }
         }
 
-        float s[kR][GT];
 #pragma unroll
-        for (int u = 0; u < kR; ++u) {
-            float kf[8];
-            unpack8<BF16>(kv[u], kf);
+        for (int ti = 0; ti < TI; ++ti) {
+            // ---- scores of 16 tokens x 16 columns on the matrix core
+            f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) c = mfma_16x16x32<BF16>(kvec[ti][j], qv[j], c);
+
+            // ---- running softmax of (head n mod GT, row group tg)
+            float s[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[i] = tok_ok[ti][i] ? c[i] * p.scale_log2e : -INFINITY;
+            const float mn = fmaxf(fmaxf(m_own, fmaxf(s[0], s[1])), fmaxf(s[2], s[3]));
+            const float alpha = exp2f(m_own - mn);
+            float pr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pr[i] = exp2f(s[i] - mn);
+            l_own = l_own * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+            m_own = mn;
+
+            // ---- acc[g] = acc[g] * alpha_g + sum_i p[g][i] * V[i]
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
-                float d = 0.f;
+                const float ag = head_bcast<GT>(alpha, g);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) d = fmaf(qf[g][i], kf[i], d);
-#pragma unroll
-                for (int off = 1; off < LPR; off <<= 1) d += __shfl_xor(d, off);
-                s[u][g] = ok[u] ? d : -INFINITY;
+                for (int e = 0; e < AE; ++e) acc[g][e] *= ag;
             }
-        }
-
-        float pr[kR][GT];
 #pragma unroll
-        for (int g = 0; g < GT; ++g) {
-            float mn = m[g];
+            for (int u = 0; u < NU; ++u) {
+                const float pi = TPL == 1 ? pr[u] : (half ? pr[(2 * u + 1) & 3] : pr[(2 * u) & 3]);
+                float vf[NV][8];
 #pragma unroll
-            for (int u = 0; u < kR; ++u) mn = fmaxf(mn, s[u][g]);
-            const float alpha = exp2f(m[g] - mn);
-            float ps = 0.f;
+                for (int w = 0; w < NV; ++w) unpack8<BF16>(vvec[ti][u][w], vf[w]);
 #pragma unroll
-            for (int u = 0; u < kR; ++u) {
-                pr[u][g] = exp2f(s[u][g] - mn);
-                ps += pr[u][g];
+                for (int g = 0; g < GT; ++g) {
+                    const float pg = head_bcast<GT>(pi, g);
+#pragma unroll
+                    for (int w = 0; w < NV; ++w)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[g][w * 8 + e] = fmaf(pg, vf[w][e], acc[g][w * 8 + e]);
+                }
             }
-            l[g] = l[g] * alpha + ps;
-            m[g] = mn;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[g][i] *= alpha;
-        }
-#pragma unroll
-        for (int u = 0; u < kR; ++u) {
-            float vf[8];
-            unpack8<BF16>(vv[u], vf);
-#pragma unroll
-            for (int g = 0; g < GT; ++g)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[g][i] = fmaf(pr[u][g], vf[i], acc[g][i]);
         }
     }
 
-    // Merge the lane groups of this wavefront (lanes LPR, 2*LPR, ... apart hold the same d positions).
+    // ---- every lane gets (m, l) of all heads of its row group; then row groups are merged
+    float mg[GT], lg[GT];
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
+    for (int g = 0; g < GT; ++g) {
+        mg[g] = head_bcast<GT>(m_own, g);
+        lg[g] = head_bcast<GT>(l_own, g);
+    }
+    if (TPL == 2) {  // the two halves of a row group share (m, l) and hold different tokens of the same d
+#pragma unroll
+        for (int g = 0; g < GT; ++g)
+#pragma unroll
+            for (int e = 0; e < AE; ++e) acc[g][e] += __shfl_xor(acc[g][e], 8);
+    }
+#pragma unroll
+    for (int off = 16; off < 64; off <<= 1) {
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            const float m2 = __shfl_xor(m[g], off), l2 = __shfl_xor(l[g], off);
-            float a2[8];
+            const float m2 = __shfl_xor(mg[g], off), l2 = __shfl_xor(lg[g], off);
+            float a2[AE];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) a2[i] = __shfl_xor(acc[g][i], off);
-            merge<8>(m[g], l[g], acc[g], m2, l2, a2);
+            for (int e = 0; e < AE; ++e) a2[e] = __shfl_xor(acc[g][e], off);
+            merge<AE>(mg[g], lg[g], acc[g], m2, l2, a2);
         }
     }
 
-    // Merge the wavefronts through LDS.
+    // ---- merge the wavefronts through LDS
     __shared__ float sh_acc[kWaves][GT][D];
     __shared__ float sh_ml[kWaves][GT][2];
-    if (rg == 0) {
+    if (tg == 0 && half == 0) {
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) sh_acc[wave][g][lr * 8 + i] = acc[g][i];
-            if (lr == 0) { sh_ml[wave][g][0] = m[g]; sh_ml[wave][g][1] = l[g]; }
+            for (int w = 0; w < NV; ++w)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sh_acc[wave][g][(lr + w * LPRV) * 8 + e] = acc[g][w * 8 + e];
+            if (n == 0) { sh_ml[wave][g][0] = mg[g]; sh_ml[wave][g][1] = lg[g]; }
         }
     }
     __syncthreads();
@@ -225,8 +304,9 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
 }
 
 // out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup of 256 threads per (hq, b).  The split weights
-// exp2(m_s - M) are computed once, in parallel over the splits, and kept in LDS; then thread d sums
-// its column over the splits with independent (pipelined) loads.
+// exp2(m_s - M) are computed once, in parallel over the splits, and kept in LDS.  Threads are then laid
+// out as (d, split group): group k sums splits k, k+NG, ... of column d with independent loads, and
+// the NG partial sums are added through LDS.
 constexpr int kCombineThreads = 256;
 constexpr int kMaxSplits = 1024;
 
@@ -236,6 +316,7 @@ kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restri
 {
     __shared__ float w[kMaxSplits];
     __shared__ float red[kCombineThreads / 64];
+    __shared__ float colsum[kCombineThreads];
     __shared__ float sh_M, sh_L;
     const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const long long o = ((long long)b * Hq + hq) * n_splits;
@@ -271,10 +352,16 @@ kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restri
     }
     __syncthreads();
     const float L = sh_L;
-    for (int d = tid; d < D; d += kCombineThreads) {
-        float A = 0.f;
+
+    const int NG = kCombineThreads / D;  // D is 64, 128 or 256
+    const int d = tid % D, grp = tid / D;
+    float A = 0.f;
 #pragma unroll 8
-        for (int s = 0; s < n_splits; ++s) A = fmaf(part_acc[(o + s) * D + d], w[s], A);
+    for (int s = grp; s < n_splits; s += NG) A = fmaf(part_acc[(o + s) * D + d], w[s], A);
+    colsum[tid] = A;
+    __syncthreads();
+    if (grp == 0) {
+        for (int k = 1; k < NG; ++k) A += colsum[k * D + d];
         const float r = L > 0.f ? A / L : 0.f;
         const long long oi = ((long long)b * Hq + hq) * D + d;
         if (out_mode == 0) ((float *)out)[oi] = r;
@@ -286,18 +373,19 @@ kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restri
 int pick_gt(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
 
 // Tokens per split: a multiple of the rows one workgroup iteration covers.
-int split_quantum(int D) { return kWaves * (64 / (D / 8)) * kR; }
+int split_quantum(int D) { return kWaves * kTile * tiles_per_iter(D); }
 
 int choose_splits(const kv_plan *p, int max_len)
 {
     if (max_len <= 0) return 1;
     const int q = split_quantum(p->D);
     const long long groups = (long long)p->B * (p->Hq / pick_gt(p->Hq / p->H));
-    // aim at ~4 workgroups per compute unit, at least 2 iterations each
-    long long want = std::max<long long>(1, (1024 + groups - 1) / groups);
-    const long long max_by_len = std::max<long long>(1, (long long)max_len / (2 * q));
+    // about two workgroups per compute unit (measured best at the 4K, 8K and 32K shapes), and no split
+    // shorter than one workgroup iteration
+    long long want = std::max<long long>(1, (512 + groups - 1) / groups);
+    const long long max_by_len = std::max<long long>(1, (long long)max_len / q);
     want = std::min(want, max_by_len);
-    return (int)std::min<long long>(want, 1024);
+    return (int)std::min<long long>(want, kMaxSplits);
 }
 
 int split_tokens_for(const kv_plan *p, int n_splits, int max_len)
@@ -308,24 +396,24 @@ int split_tokens_for(const kv_plan *p, int n_splits, int max_len)
     return (int)std::max<long long>(st, q);
 }
 
-template <int LPR, int GT>
+template <int D, int GT>
 void launch_partial(bool bf16, bool paged, dim3 grid, hipStream_t st, const AttnParams &a)
 {
     if (bf16) {
-        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<LPR, GT, true, true>), grid, dim3(kThreads), 0, st, a);
-        else hipLaunchKernelGGL((kv_attn_partial_kernel<LPR, GT, true, false>), grid, dim3(kThreads), 0, st, a);
+        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, true, true>), grid, dim3(kThreads), 0, st, a);
+        else hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, true, false>), grid, dim3(kThreads), 0, st, a);
     } else {
-        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<LPR, GT, false, true>), grid, dim3(kThreads), 0, st, a);
-        else hipLaunchKernelGGL((kv_attn_partial_kernel<LPR, GT, false, false>), grid, dim3(kThreads), 0, st, a);
+        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, false, true>), grid, dim3(kThreads), 0, st, a);
+        else hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, false, false>), grid, dim3(kThreads), 0, st, a);
     }
 }
 
-template <int LPR>
+template <int D>
 void launch_partial_gt(int gt, bool bf16, bool paged, dim3 grid, hipStream_t st, const AttnParams &a)
 {
-    if (gt == 4) launch_partial<LPR, 4>(bf16, paged, grid, st, a);
-    else if (gt == 2) launch_partial<LPR, 2>(bf16, paged, grid, st, a);
-    else launch_partial<LPR, 1>(bf16, paged, grid, st, a);
+    if (gt == 4) launch_partial<D, 4>(bf16, paged, grid, st, a);
+    else if (gt == 2) launch_partial<D, 2>(bf16, paged, grid, st, a);
+    else launch_partial<D, 1>(bf16, paged, grid, st, a);
 }
 
 }  // namespace
@@ -402,9 +490,9 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf16 = p->dtype == KV_BF16;
     dim3 grid((unsigned)ns, (unsigned)(p->Hq / gt), (unsigned)p->B);
-    if (p->D == 64) launch_partial_gt<8>(gt, bf16, paged, grid, st, a);
-    else if (p->D == 128) launch_partial_gt<16>(gt, bf16, paged, grid, st, a);
-    else launch_partial_gt<32>(gt, bf16, paged, grid, st, a);
+    if (p->D == 64) launch_partial_gt<64>(gt, bf16, paged, grid, st, a);
+    else if (p->D == 128) launch_partial_gt<128>(gt, bf16, paged, grid, st, a);
+    else launch_partial_gt<256>(gt, bf16, paged, grid, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
 
