@@ -85,13 +85,13 @@ def cpu_baseline(cfg, W, budget_s: float = 20.0):
 
 
 def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps: int):
-    """Resident-KV leg: every kernel of the path launched back to back on whole tensors, rotating over
+    """Resident-KV leg: every kernel of the path launched back to back on whole layers, rotating over
     all layers (so each launch touches memory no earlier launch left in the last-level cache), no DMA
     in flight.  Each kind is bracketed by events on the stream it is launched on (the default stream,
     which is also PyTorch's current stream here); the figure is the average per launch, gaps included."""
     L = cfg.n_layers
-    image = int(info.tensor_blocks) * cfg.sector_bytes
-    n_img = max(2, min(2 * L, (1 << 30) // image))        # rotating extent images, about 1 GiB
+    image = 2 * int(info.tensor_blocks) * cfg.sector_bytes  # K image followed by V image of one layer
+    n_img = max(2, min(L, (1 << 30) // image))            # rotating image pairs, about 1 GiB
     imgs = [torch.empty(image, dtype=torch.uint8, device="cuda") for _ in range(n_img)]
     max_len = max(lens)
     ws = torch.empty(kv.kv_decode_attn_workspace(plan, 0, max_len), dtype=torch.uint8, device="cuda")
@@ -108,19 +108,13 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / (reps * n_launches)   # microseconds per launch
 
-    def pack_all():
-        i = 0
+    def pack_all():      # one launch per layer: K and V together, as the pipeline issues them
         for l in range(L):
-            for kind in (0, 1):
-                kv.kv_offload_pack(plan, l, kind, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[i % n_img])
-                i += 1
+            kv.kv_offload_pack(plan, l, kv.KV_KV, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[l % n_img])
 
     def unpack_all():
-        i = 0
         for l in range(L):
-            for kind in (0, 1):
-                kv.kv_reload_unpack(plan, l, kind, imgs[i % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
-                i += 1
+            kv.kv_reload_unpack(plan, l, kv.KV_KV, imgs[l % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
 
     def attn_all():
         for l in range(L):
@@ -132,7 +126,7 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         for i in range(8):
             imgs[(i + 1) % n_img].copy_(imgs[i % n_img])
 
-    return {"pack_us": timed(pack_all, 2 * L), "unpack_us": timed(unpack_all, 2 * L), "attn_us": timed(attn_all, L),
+    return {"pack_us": timed(pack_all, L), "unpack_us": timed(unpack_all, L), "attn_us": timed(attn_all, L),
             "copy_ref_us": timed(copy_ref, 8), "copy_ref_bytes": image}
 
 
@@ -306,13 +300,13 @@ def main():
     if args.leg in ("both", "kernels"):
         kl = kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps=max(3, args.steps))
         where = "resident-KV leg: whole-tensor launches back to back, rotating over all layers"
-        rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], tensor_payload + tensor_image, where),
-              roof("kv_layout_kernel<unpack>", kl["unpack_us"], 2 * tensor_payload, where),
+        rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], 2 * (tensor_payload + tensor_image), where),
+              roof("kv_layout_kernel<unpack>", kl["unpack_us"], 4 * tensor_payload, where),
               roof("kv_attn_partial_kernel+kv_attn_combine_kernel", kl["attn_us"], 2 * tensor_payload, where)]
         res["rooflines"] = rl
         res["decode_attn_us_per_layer"] = round(kl["attn_us"], 2)
         # the dominant kernel of a step: the one with the most GPU time over its launches
-        tot = [kl["pack_us"] * 2 * L, kl["unpack_us"] * 2 * L, kl["attn_us"] * L]
+        tot = [kl["pack_us"] * L, kl["unpack_us"] * L, kl["attn_us"] * L]
         dom = rl[max(range(3), key=lambda i: tot[i])]
         res["roofline"] = {key: dom[key] for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "where")}
     else:

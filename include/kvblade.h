@@ -45,6 +45,7 @@ extern "C" {
 
 #define KV_K 0
 #define KV_V 1
+#define KV_KV 2 /* pack / unpack only: K and V of the layer in one launch, V's image after K's */
 
 #define KV_LAYOUT_BHSD 0  /* strided [B, H, S_alloc, D], d contiguous */
 #define KV_LAYOUT_PAGED 1 /* block pool [n_pool, H, block_tokens, D] + block table */
@@ -156,7 +157,8 @@ typedef struct kv_attn_args {
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 
 typedef struct kv_pipe_opts {
-    int32_t span_chunks;  /* chunks per kernel launch and staging slot; 0 = a whole tensor */
+    int32_t span_chunks;  /* chunks of one tensor per kernel launch and staging slot; 0 = a whole layer
+                             (K and V in one launch) */
     int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
     uint32_t flags;       /* KV_PIPE_* */
     int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (2 D2H, 4 H2D);
@@ -236,6 +238,8 @@ int kv_plan_chunk_cmds(const kv_plan_t *plan, int layer, int kind, int seq, int 
  *   seq = KV_SEQ_ALL (tok0 = ntok = 0): the whole extent image, n_blocks*sector bytes: rows
  *     [0, len_b) of every sequence (src->seq_lens_host, <= capacity; uniform in token-major) and
  *     zeros up to each (sub-)extent's end.
+ *   kind = KV_KV moves both tensors of the layer in one launch: dst_dev holds K's bytes as above and
+ *     V's bytes right after them (at n_blocks*sector, or at req_bytes for a row range).
  * src: host struct, device buffers; dst_dev: device, 16-byte aligned, dst_bytes >= bytes written
  * (else KV_ENOSPC).  Rows must exist in the source (BHSD: < s_alloc; paged: < seq_lens_host[b]) else
  * KV_ERANGE.  Nothing is launched on error.

@@ -18,7 +18,7 @@ KV_OK, KV_EINVAL, KV_EALIGN, KV_ERANGE, KV_ENOSPC, KV_EHIP = 0, -1, -2, -3, -4, 
 KV_F16, KV_BF16 = 0, 1
 KV_TOKEN_MAJOR, KV_PER_SEQ = 0, 1
 KV_PATH_DIRECT, KV_PATH_PAGECACHE = 0, 1
-KV_K, KV_V = 0, 1
+KV_K, KV_V, KV_KV = 0, 1, 2
 KV_LAYOUT_BHSD, KV_LAYOUT_PAGED = 0, 1
 KV_SEQ_ALL = -1
 KV_UNBOUNDED = 2**64 - 1

@@ -24,7 +24,7 @@ constexpr int kMaxSegs = 32;
 
 // Attention-side addressing, in 16-byte vectors.
 struct SrcDesc {
-    u32x4 *base;
+    u32x4 *base[2];        // K and V buffers of the layer
     long long sb, sh, ss;  // strided layout: vectors per batch / head / token step
     const int *table;      // paged layout
     int max_blocks, bt, bt_shift, n_pool;
@@ -38,6 +38,7 @@ struct Seg {
     unsigned int pad_vecs;       // zero vectors to write (pack only)
     int b;                       // sequence, or -1: the batch index is part of the row position
     int tok0, ntok;
+    int which;                   // 0: the layer's K buffer, 1: its V buffer
 };
 
 struct SegTable {
@@ -62,6 +63,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
 {
     const Seg sg = segs.seg[blockIdx.y];
     const int tid = threadIdx.x;
+    u32x4 *const base = s.base[sg.which];
 
     if (PACK && sg.pad_vecs) {
         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -112,7 +114,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const unsigned long long i = sg.img_off + (unsigned long long)(t0 + u * TY) * rowv + r;
-                if (ok[u]) v[u] = PACK ? ld<NTL>(s.base + a[u]) : ld<NTL>(img + i);
+                if (ok[u]) v[u] = PACK ? ld<NTL>(base + a[u]) : ld<NTL>(img + i);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -123,7 +125,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
                     const u32x4 z = {0u, 0u, 0u, 0u};
                     if (in) st<NTS>(img + i, ok[u] ? v[u] : z);
                 } else if (ok[u]) {
-                    st<NTS>(s.base + a[u], v[u]);
+                    st<NTS>(base + a[u], v[u]);
                 }
             }
         }
@@ -172,10 +174,11 @@ int check_rows(const kv_plan *p, const kv_view_t *v, int b, int tok0, int ntok)
     return KV_OK;
 }
 
-SrcDesc make_src(const kv_plan *p, const kv_view_t *v, int layer, int kind)
+SrcDesc make_src(const kv_plan *p, const kv_view_t *v, int layer)
 {
     SrcDesc s{};
-    s.base = (u32x4 *)(kind == KV_K ? v->k_layers[layer] : v->v_layers[layer]);
+    s.base[0] = (u32x4 *)v->k_layers[layer];
+    s.base[1] = (u32x4 *)v->v_layers[layer];
     s.H = p->H;
     s.dvec = p->D / 8;
     if (v->layout == KV_LAYOUT_BHSD) {
@@ -219,8 +222,7 @@ void launch_u(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const 
 }
 
 template <bool PACK>
-int launch(const kv_plan *p, const kv_view_t *v, int layer, int kind, const Seg *segs, int nseg, void *img,
-           hipStream_t stream)
+int launch(const kv_plan *p, const kv_view_t *v, int layer, const Seg *segs, int nseg, void *img, hipStream_t stream)
 {
     const int rowv = (int)(p->row_bytes / 16);
     int rx_log2 = 0;
@@ -229,7 +231,7 @@ int launch(const kv_plan *p, const kv_view_t *v, int layer, int kind, const Seg 
     const int U = g_unroll == 8 ? 8 : (g_unroll == 2 ? 2 : 4);
     int tpb = (int)std::max<long long>(1, g_tile_bytes / (long long)p->row_bytes);
     tpb = (tpb + TY * U - 1) / (TY * U) * (TY * U);
-    const SrcDesc s = make_src(p, v, layer, kind);
+    const SrcDesc s = make_src(p, v, layer);
     const bool paged = v->layout == KV_LAYOUT_PAGED;
 
     for (int g0 = 0; g0 < nseg; g0 += kMaxSegs) {
@@ -254,18 +256,21 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
         size_t img_bytes, void *hip_stream)
 {
     if (!p || !img) return KV_EINVAL;
-    if (kind != KV_K && kind != KV_V) return KV_EINVAL;
+    if (kind != KV_K && kind != KV_V && kind != KV_KV) return KV_EINVAL;
     if ((uintptr_t)img & 15) return KV_EINVAL;
     int rc = check_view(p, v, layer);
     if (rc != KV_OK) return rc;
     if (p->row_bytes / 16 > (uint64_t)INT_MAX) return KV_EINVAL;
     hipStream_t stream = (hipStream_t)hip_stream;
     const uint64_t sec = (uint64_t)p->sector;
+    const int first = kind == KV_V ? 1 : 0, last = kind == KV_K ? 0 : 1;  // KV_KV: K image, then V image
+    const uint64_t n_img = (uint64_t)(last - first + 1);
 
     std::vector<Seg> segs;
     if (seq == KV_SEQ_ALL && tok0 == 0 && ntok == 0) {
-        // Whole extent image.
-        if (img_bytes < p->tensor_blocks * sec) return KV_ENOSPC;
+        // Whole extent image(s).
+        const uint64_t image = p->tensor_blocks * sec;
+        if (img_bytes < n_img * image) return KV_ENOSPC;
         if (p->mode == KV_TOKEN_MAJOR) {
             const int len = v->seq_lens_host[0];
             for (int b = 0; b < p->B; ++b)
@@ -273,44 +278,53 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
             if (len < 0 || len > p->cap[0]) return KV_ERANGE;
             rc = check_rows(p, v, -1, 0, len);
             if (rc != KV_OK) return rc;
-            Seg s{};
-            s.img_off = 0; s.b = -1; s.tok0 = 0; s.ntok = len;
-            s.pad_off = (uint64_t)len * p->row_bytes / 16;
-            s.pad_vecs = (unsigned)((p->tensor_blocks * sec - (uint64_t)len * p->row_bytes) / 16);
-            segs.push_back(s);
-        } else {
-            for (int b = 0; b < p->B; ++b) {
-                const int len = v->seq_lens_host[b];
-                if (len < 0 || len > p->cap[b]) return KV_ERANGE;
-                rc = check_rows(p, v, b, 0, len);
-                if (rc != KV_OK) return rc;
-                const uint64_t sub_bytes = kvb::round_up((uint64_t)p->cap[b] * p->row_bytes, sec);
+            for (int w = first; w <= last; ++w) {
                 Seg s{};
-                s.img_off = p->seq_base[b] * sec / 16;
-                s.b = b; s.tok0 = 0; s.ntok = len;
+                s.img_off = (uint64_t)(w - first) * image / 16;
+                s.b = -1; s.tok0 = 0; s.ntok = len; s.which = w;
                 s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
-                s.pad_vecs = (unsigned)((sub_bytes - (uint64_t)len * p->row_bytes) / 16);
-                if (len > 0 || s.pad_vecs > 0) segs.push_back(s);
+                s.pad_vecs = (unsigned)((image - (uint64_t)len * p->row_bytes) / 16);
+                segs.push_back(s);
+            }
+        } else {
+            for (int w = first; w <= last; ++w) {
+                for (int b = 0; b < p->B; ++b) {
+                    const int len = v->seq_lens_host[b];
+                    if (len < 0 || len > p->cap[b]) return KV_ERANGE;
+                    rc = check_rows(p, v, b, 0, len);
+                    if (rc != KV_OK) return rc;
+                    const uint64_t sub_bytes = kvb::round_up((uint64_t)p->cap[b] * p->row_bytes, sec);
+                    Seg s{};
+                    s.img_off = ((uint64_t)(w - first) * image + p->seq_base[b] * sec) / 16;
+                    s.b = b; s.tok0 = 0; s.ntok = len; s.which = w;
+                    s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
+                    s.pad_vecs = (unsigned)((sub_bytes - (uint64_t)len * p->row_bytes) / 16);
+                    if (len > 0 || s.pad_vecs > 0) segs.push_back(s);
+                }
             }
         }
     } else {
         kvb::RowRange r;
         rc = kvb::resolve_rows(p, seq, tok0, ntok, &r);
         if (rc != KV_OK) return rc;
-        if (img_bytes < (PACK ? r.req_bytes : r.payload)) return KV_ENOSPC;
+        // with KV_KV the V range follows the K range at req_bytes
+        if (img_bytes < (n_img - 1) * r.req_bytes + (PACK ? r.req_bytes : r.payload)) return KV_ENOSPC;
         const int b = p->mode == KV_TOKEN_MAJOR ? -1 : r.b;
         rc = check_rows(p, v, b, tok0, ntok);
         if (rc != KV_OK) return rc;
-        Seg s{};
-        s.img_off = 0; s.b = b; s.tok0 = tok0; s.ntok = ntok;
-        s.pad_off = r.payload / 16;
-        s.pad_vecs = (unsigned)((r.req_bytes - r.payload) / 16);
-        segs.push_back(s);
+        for (int w = first; w <= last; ++w) {
+            Seg s{};
+            s.img_off = (uint64_t)(w - first) * r.req_bytes / 16;
+            s.b = b; s.tok0 = tok0; s.ntok = ntok; s.which = w;
+            s.pad_off = s.img_off + r.payload / 16;
+            s.pad_vecs = (unsigned)((r.req_bytes - r.payload) / 16);
+            segs.push_back(s);
+        }
     }
     if (!PACK)
         for (Seg &s : segs) s.pad_vecs = 0;
     if (segs.empty()) return KV_OK;
-    return launch<PACK>(p, v, layer, kind, segs.data(), (int)segs.size(), img, stream);
+    return launch<PACK>(p, v, layer, segs.data(), (int)segs.size(), img, stream);
 }
 
 }  // namespace

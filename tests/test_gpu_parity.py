@@ -84,6 +84,36 @@ def test_pack_chunk_ranges(case):
             assert _guards_intact(buf, nbytes)
 
 
+def test_pack_unpack_both_tensors_in_one_launch(case):
+    """kind = KV_KV: K's image, then V's, from one launch; whole extents and one chunk range."""
+    r = case.ref
+    ext_bytes = r.n_blocks_tensor * r.lba_size
+    layer = case.cfg.n_layers - 1
+    buf, dst = _guarded(2 * ext_bytes)
+    kv.kv_offload_pack(case.plan, layer, kv.KV_KV, case.view, kv.KV_SEQ_ALL, 0, 0, dst)
+    torch.cuda.synchronize()
+    want_k, want_v = case.expected_extent(layer, 0), case.expected_extent(layer, 1)
+    got = dst.cpu().numpy()
+    assert np.array_equal(got[:ext_bytes], want_k) and np.array_equal(got[ext_bytes:], want_v)
+    assert _guards_intact(buf, 2 * ext_bytes)
+
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    kv.kv_reload_unpack(case.plan, layer, kv.KV_KV, dst, view, kv.KV_SEQ_ALL, 0, 0)
+    torch.cuda.synchronize()
+    _check_restored(case, k_new, v_new, [layer])
+
+    c = kv.kv_plan_chunk_cmds(case.plan, layer, 0, 0)[-1]          # the ragged tail chunk of sequence 0
+    nbytes = (c.nlb + 1) * r.lba_size
+    buf, dst = _guarded(2 * nbytes)
+    kv.kv_offload_pack(case.plan, layer, kv.KV_KV, case.view, 0, c.tok0, c.ntok, dst)
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy()
+    assert np.array_equal(got[:nbytes], want_k[c.buf_off:c.buf_off + nbytes])
+    assert np.array_equal(got[nbytes:], want_v[c.buf_off:c.buf_off + nbytes])
+    assert _guards_intact(buf, 2 * nbytes)
+
+
 # ------------------------------------------------------------------------------------------ unpack
 def _check_restored(case, k_new, v_new, layers, fill=0x7E7E):
     cfg = case.cfg
@@ -185,7 +215,7 @@ def test_kernel_argument_errors(case):
 
     cap = case.lens[0]
     assert code(lambda: kv.kv_offload_pack(case.plan, 99, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst)) == kv.KV_ERANGE
-    assert code(lambda: kv.kv_offload_pack(case.plan, 0, 2, case.view, kv.KV_SEQ_ALL, 0, 0, dst)) == kv.KV_EINVAL
+    assert code(lambda: kv.kv_offload_pack(case.plan, 0, 3, case.view, kv.KV_SEQ_ALL, 0, 0, dst)) == kv.KV_EINVAL
     assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, 0, 0, cap + 1, dst)) == kv.KV_ERANGE
     assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst[:4096])) == kv.KV_ENOSPC
     assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst[8:])) == kv.KV_EINVAL
