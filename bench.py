@@ -90,8 +90,11 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
     in flight.  Each kind is bracketed by events on the stream it is launched on (the default stream,
     which is also PyTorch's current stream here); the figure is the average per launch, gaps included."""
     L = cfg.n_layers
-    image = 2 * int(info.tensor_blocks) * cfg.sector_bytes  # K image followed by V image of one layer
-    n_img = max(2, min(L, (1 << 30) // image))            # rotating image pairs, about 1 GiB
+    tensor_image = int(info.tensor_blocks) * cfg.sector_bytes
+    pair = 2 * tensor_image <= (256 << 20)                # the pipeline's rule: K and V share a launch up to 256 MiB
+    kinds = [kv.KV_KV] if pair else [kv.KV_K, kv.KV_V]
+    image = (2 if pair else 1) * tensor_image
+    n_img = max(2, min(L * len(kinds), (1 << 30) // image))   # rotating extent images, about 1 GiB
     imgs = [torch.empty(image, dtype=torch.uint8, device="cuda") for _ in range(n_img)]
     max_len = max(lens)
     ws = torch.empty(kv.kv_decode_attn_workspace(plan, 0, max_len), dtype=torch.uint8, device="cuda")
@@ -108,13 +111,19 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / (reps * n_launches)   # microseconds per launch
 
-    def pack_all():      # one launch per layer: K and V together, as the pipeline issues them
+    def pack_all():      # the launches the pipeline issues: whole tensors, or K and V of a layer together
+        i = 0
         for l in range(L):
-            kv.kv_offload_pack(plan, l, kv.KV_KV, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[l % n_img])
+            for kind in kinds:
+                kv.kv_offload_pack(plan, l, kind, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[i % n_img])
+                i += 1
 
     def unpack_all():
+        i = 0
         for l in range(L):
-            kv.kv_reload_unpack(plan, l, kv.KV_KV, imgs[l % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
+            for kind in kinds:
+                kv.kv_reload_unpack(plan, l, kind, imgs[i % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
+                i += 1
 
     def attn_all():
         for l in range(L):
@@ -126,8 +135,10 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         for i in range(8):
             imgs[(i + 1) % n_img].copy_(imgs[i % n_img])
 
-    return {"pack_us": timed(pack_all, L), "unpack_us": timed(unpack_all, L), "attn_us": timed(attn_all, L),
-            "copy_ref_us": timed(copy_ref, 8), "copy_ref_bytes": image}
+    n = L * len(kinds)
+    return {"pack_us": timed(pack_all, n), "unpack_us": timed(unpack_all, n), "attn_us": timed(attn_all, L),
+            "copy_ref_us": timed(copy_ref, 8), "copy_ref_bytes": image, "tensors_per_launch": 2 // len(kinds),
+            "layout_launches": n}
 
 
 def main():
@@ -234,9 +245,23 @@ def main():
         res["value"] = round(2 * payload * args.steps / elapsed / 1e9, 3)
 
         # the timed work's result: the reloaded cache must equal the source bit for bit
+        if cfg.layout == W.PAGED:   # slots past a sequence's length are not part of the cache
+            bt = cfg.block_tokens
+            valid = torch.zeros((n_pool, bt), dtype=torch.bool)
+            for b, n in enumerate(lens):
+                nb = -(-n // bt)
+                valid[table[b, :nb].long()] = True
+                if n % bt:
+                    valid[table[b, nb - 1].long(), n % bt:] = False
+            mask = valid.cuda()[:, None, :, None]
+        else:
+            mask = None
         for l in (0, L - 1):
-            assert torch.equal(k[l].view(torch.int16), k2[l].view(torch.int16)), "reload differs from source"
-            assert torch.equal(v[l].view(torch.int16), v2[l].view(torch.int16)), "reload differs from source"
+            for a, b_ in ((k[l], k2[l]), (v[l], v2[l])):
+                a, b_ = a.view(torch.int16), b_.view(torch.int16)
+                if mask is not None:
+                    a, b_ = torch.where(mask, a, 0), torch.where(mask, b_, 0)
+                assert torch.equal(a, b_), "reload differs from source"
 
         off_s = sum(a.wall_s for a, _ in stats) / args.steps
         rel_s = sum(b.wall_s for _, b in stats) / args.steps
@@ -300,13 +325,14 @@ def main():
     if args.leg in ("both", "kernels"):
         kl = kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps=max(3, args.steps))
         where = "resident-KV leg: whole-tensor launches back to back, rotating over all layers"
-        rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], 2 * (tensor_payload + tensor_image), where),
-              roof("kv_layout_kernel<unpack>", kl["unpack_us"], 4 * tensor_payload, where),
+        tpl = kl["tensors_per_launch"]
+        rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], tpl * (tensor_payload + tensor_image), where),
+              roof("kv_layout_kernel<unpack>", kl["unpack_us"], tpl * 2 * tensor_payload, where),
               roof("kv_attn_partial_kernel+kv_attn_combine_kernel", kl["attn_us"], 2 * tensor_payload, where)]
         res["rooflines"] = rl
         res["decode_attn_us_per_layer"] = round(kl["attn_us"], 2)
         # the dominant kernel of a step: the one with the most GPU time over its launches
-        tot = [kl["pack_us"] * L, kl["unpack_us"] * L, kl["attn_us"] * L]
+        tot = [kl["pack_us"] * kl["layout_launches"], kl["unpack_us"] * kl["layout_launches"], kl["attn_us"] * L]
         dom = rl[max(range(3), key=lambda i: tot[i])]
         res["roofline"] = {key: dom[key] for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "where")}
     else:

@@ -266,7 +266,8 @@ int kv_reload_unpack(const kv_plan_t *plan, int layer, int kind, const void *src
  */
 int kv_decode_attn(const kv_plan_t *plan, const kv_view_t *kv, int layer, const void *q, void *out,
                    int out_dtype, int n_splits, void *workspace, size_t ws_bytes, void *hip_stream);
-/* Bytes of workspace kv_decode_attn needs for up to max_len tokens per sequence (n_splits 0 = chosen). */
+/* Bytes of workspace kv_decode_attn needs for up to max_len tokens per sequence (n_splits 0 = enough
+ * for whatever split count the library chooses at that length). */
 size_t kv_decode_attn_workspace(const kv_plan_t *plan, int n_splits, int max_len);
 
 /* ------------------------------------------------------------------------------------------ */

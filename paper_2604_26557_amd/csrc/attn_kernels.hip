@@ -375,17 +375,25 @@ int pick_gt(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
 // Tokens per split: a multiple of the rows one workgroup iteration covers.
 int split_quantum(int D) { return kWaves * kTile * tiles_per_iter(D); }
 
-int choose_splits(const kv_plan *p, int max_len)
+// Most splits the automatic choice can make for sequences of up to max_len tokens (sizes the workspace).
+int max_auto_splits(const kv_plan *p, int max_len)
+{
+    const int q = split_quantum(p->D);
+    return (int)std::min<long long>(kMaxSplits, std::max<long long>(1, ((long long)max_len + q - 1) / q));
+}
+
+// Split length from the total token count, so that about 512 workgroups (two per compute unit; the
+// measured best at the 4K, 8K and 32K shapes) have tokens to read even when the batch is ragged;
+// never shorter than one workgroup iteration.
+int choose_splits(const kv_plan *p, long long total_tokens, int max_len)
 {
     if (max_len <= 0) return 1;
     const int q = split_quantum(p->D);
-    const long long groups = (long long)p->B * (p->Hq / pick_gt(p->Hq / p->H));
-    // about two workgroups per compute unit (measured best at the 4K, 8K and 32K shapes), and no split
-    // shorter than one workgroup iteration
-    long long want = std::max<long long>(1, (512 + groups - 1) / groups);
-    const long long max_by_len = std::max<long long>(1, (long long)max_len / q);
-    want = std::min(want, max_by_len);
-    return (int)std::min<long long>(want, kMaxSplits);
+    const long long groups_per_seq = p->Hq / pick_gt(p->Hq / p->H);
+    long long st = (total_tokens * groups_per_seq + 511) / 512;
+    st = std::max<long long>(q, (st + q - 1) / q * q);
+    const long long ns = ((long long)max_len + st - 1) / st;
+    return (int)std::min<long long>(std::max<long long>(1, ns), max_auto_splits(p, max_len));
 }
 
 int split_tokens_for(const kv_plan *p, int n_splits, int max_len)
@@ -421,7 +429,7 @@ void launch_partial_gt(int gt, bool bf16, bool paged, dim3 grid, hipStream_t st,
 extern "C" size_t kv_decode_attn_workspace(const kv_plan_t *p, int n_splits, int max_len)
 {
     if (!p || n_splits < 0 || max_len < 0) return 0;
-    const int ns = n_splits > 0 ? n_splits : choose_splits(p, max_len);
+    const int ns = n_splits > 0 ? n_splits : max_auto_splits(p, max_len);
     return (size_t)p->B * p->Hq * ns * (p->D + 2) * sizeof(float);
 }
 
@@ -440,10 +448,12 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
     if (p->B > 65535 || p->Hq > 65535) return KV_EINVAL;
 
     int max_len = 0;
+    long long total_len = 0;
     for (int b = 0; b < p->B; ++b) {
         const int len = kv->seq_lens_host[b];
         if (len < 0) return KV_EINVAL;
         max_len = std::max(max_len, len);
+        total_len += len;
     }
     AttnParams a{};
     const bool paged = kv->layout == KV_LAYOUT_PAGED;
@@ -472,7 +482,7 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
         return KV_EINVAL;
     }
 
-    const int ns = n_splits > 0 ? n_splits : choose_splits(p, max_len);
+    const int ns = n_splits > 0 ? n_splits : choose_splits(p, total_len, max_len);
     const size_t need = (size_t)p->B * p->Hq * ns * (p->D + 2) * sizeof(float);
     if (ws_bytes < need) return KV_ENOSPC;
 
