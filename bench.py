@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--host-workers", type=int, default=0)
     ap.add_argument("--span-chunks", type=int, default=0)
+    ap.add_argument("--attn-from-extent", action="store_true",
+                    help="reload: decode attention reads the staged extent images, nothing is unpacked")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -207,7 +209,7 @@ def main():
                                f"{cfg.sector_bytes} B sectors",
                    "chunk_tokens": cfg.chunk_tokens, "depth": cfg.depth, "pagecache_layers": n1,
                    "span_chunks": args.span_chunks, "layout": cfg.layout, "extent_mode": cfg.extent_mode,
-                   "leg": args.leg},
+                   "leg": args.leg, "attn_from_extent": args.attn_from_extent},
     }
 
     def roof(name, us, per_launch, where):
@@ -229,7 +231,8 @@ def main():
                                    span_chunks=args.span_chunks, host_workers=args.host_workers, time_kernels=timed)
             b = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD_ATTN, 0, L, dst_view, region, arena, depth=cfg.depth,
                                    q_layers=qs, out_layers=outs, span_chunks=args.span_chunks,
-                                   host_workers=args.host_workers, time_kernels=timed)
+                                   host_workers=args.host_workers, time_kernels=timed,
+                                   attn_from_extent=args.attn_from_extent)
             return a, b
 
         for _ in range(args.warmup):
@@ -256,7 +259,7 @@ def main():
             mask = valid.cuda()[:, None, :, None]
         else:
             mask = None
-        for l in (0, L - 1):
+        for l in (() if args.attn_from_extent else (0, L - 1)):
             for a, b_ in ((k[l], k2[l]), (v[l], v2[l])):
                 a, b_ = a.view(torch.int16), b_.view(torch.int16)
                 if mask is not None:
@@ -275,7 +278,7 @@ def main():
         unpack_us, unpack_n = kstat(kv.KV_KERNEL_UNPACK, 1)
         attn_us, attn_n = kstat(kv.KV_KERNEL_ATTN_PARTIAL, 1)
         per_t_pack = pack_n / (2 * L * args.steps)
-        per_t_unpack = unpack_n / (2 * L * args.steps)
+        per_t_unpack = max(unpack_n, 1) / (2 * L * args.steps)
         where = "inside the pipeline steps (DMA in flight, GPU otherwise idle)"
         res["rooflines_in_pipeline"] = [
             roof("kv_layout_kernel<pack>", pack_us, (tensor_payload + tensor_image) / per_t_pack, where),

@@ -156,6 +156,11 @@ typedef struct kv_attn_args {
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 
+#define KV_PIPE_ATTN_FROM_EXTENT 4u /* KV_DIR_RELOAD_ATTN, token-major plans, whole-extent spans only: decode
+                                       attention reads the staged extent images directly (extent order is a
+                                       strided [B,H,S,D] view) and nothing is unpacked: the view's K/V buffers
+                                       are neither read nor written */
+
 typedef struct kv_pipe_opts {
     int32_t span_chunks;  /* chunks of one tensor per kernel launch and staging slot; 0 = a whole layer
                              (K and V in one launch) */

@@ -27,6 +27,7 @@ KV_DIR_OFFLOAD, KV_DIR_RELOAD, KV_DIR_RELOAD_ATTN = 0, 1, 2
 KV_KERNEL_PACK, KV_KERNEL_UNPACK, KV_KERNEL_ATTN_PARTIAL, KV_KERNEL_ATTN_COMBINE = 0, 1, 2, 3
 KV_PIPE_TIME_KERNELS = 1
 KV_PIPE_SERIALIZE = 2
+KV_PIPE_ATTN_FROM_EXTENT = 4
 KV_COPY_AUTO, KV_COPY_MEMCPY, KV_COPY_KERNEL = 0, 1, 2
 
 EXPORTS = [
@@ -306,7 +307,7 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
                     q_layers=None, out_layers=None, out_dtype: int = KV_OUT_F32, n_splits: int = 0,
                     span_chunks: int = 0, host_workers: int = 0, time_kernels: bool = False,
                     copy_streams: int = 0, d2h_mode: int = KV_COPY_AUTO, h2d_mode: int = KV_COPY_AUTO,
-                    serialize: bool = False) -> kv_pipe_stats_t:
+                    serialize: bool = False, attn_from_extent: bool = False) -> kv_pipe_stats_t:
     """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array."""
     def host(buf):
         if buf is None:
@@ -323,7 +324,8 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
         qa, oa = _ptr_array(q_layers), _ptr_array(out_layers)
         attn = kv_attn_args_t(qa, oa, out_dtype, n_splits)
         keep = (qa, oa)
-    opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0), copy_streams,
+    opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0)
+                          | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0), copy_streams,
                           d2h_mode, h2d_mode)
     st = kv_pipe_stats_t()
     rc = lib().kv_pipeline_run(plan.handle, direction, layer_begin, layer_end, view.ref(), rp, rb, pp, pb,

@@ -297,6 +297,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const int n_workers = opts && opts->host_workers > 0 ? opts->host_workers : 8;
     const bool time_kernels = opts && (opts->flags & KV_PIPE_TIME_KERNELS);
     const bool serialize = opts && (opts->flags & KV_PIPE_SERIALIZE);
+    const bool attn_from_extent = opts && (opts->flags & KV_PIPE_ATTN_FROM_EXTENT);
+    if (attn_from_extent && (dir != KV_DIR_RELOAD_ATTN || p->mode != KV_TOKEN_MAJOR || span_chunks != 0)) return KV_EINVAL;
     if (span_chunks < 0 || n_workers > 64) return KV_EINVAL;
     const bool offload_dir = dir == KV_DIR_OFFLOAD;
     int ns = opts ? opts->copy_streams : 0;
@@ -476,6 +478,9 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         return hipGetLastError();
     };
     unsigned used = 0;  // copy streams that carried a chunk of the current span
+    std::vector<void *> ext_k((size_t)view->n_layers, nullptr), ext_v((size_t)view->n_layers, nullptr);
+    char *ext_k_img = nullptr;
+    int ext_k_slot = -1;
 
     if (offload) {
         for (size_t c = 0; c < N && err == KV_OK; ++c) {
@@ -577,19 +582,50 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                     if (err == KV_OK) KV_HIP_SET(hipStreamWaitEvent(q->s_compute, q->ev_done[slot * kMaxCopyStreams + k], 0));
                 }
                 if (err != KV_OK) break;
-                time_begin(KV_KERNEL_UNPACK);
-                err = kv_reload_unpack(p, sp.layer, sp.kind, img, slot_bytes, view, sp.seq, sp.tok0, sp.ntok, q->s_compute);
-                time_end();
-                if (err != KV_OK) break;
-                if (stats) { stats->kernel_launches[KV_KERNEL_UNPACK]++; stats->n_spans++; }
-                KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_compute));
-                if (dir == KV_DIR_RELOAD_ATTN && sp.last_of_layer) {
-                    time_begin(KV_KERNEL_ATTN_PARTIAL);  // partial + combine bracketed together
-                    err = kv_decode_attn(p, view, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
-                                         attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
+                if (!attn_from_extent) {
+                    time_begin(KV_KERNEL_UNPACK);
+                    err = kv_reload_unpack(p, sp.layer, sp.kind, img, slot_bytes, view, sp.seq, sp.tok0, sp.ntok, q->s_compute);
                     time_end();
                     if (err != KV_OK) break;
-                    if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
+                    if (stats) { stats->kernel_launches[KV_KERNEL_UNPACK]++; stats->n_spans++; }
+                    KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_compute));
+                    if (dir == KV_DIR_RELOAD_ATTN && sp.last_of_layer) {
+                        time_begin(KV_KERNEL_ATTN_PARTIAL);  // partial + combine bracketed together
+                        err = kv_decode_attn(p, view, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
+                                             attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
+                        time_end();
+                        if (err != KV_OK) break;
+                        if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
+                    }
+                } else {
+                    // Attention straight from the staged extent images: extent order (S, B*H, D) is the
+                    // strided [B,H,S,D] view with strides (H*D, D, B*H*D), so nothing is unpacked.
+                    if (stats) stats->n_spans++;
+                    if (sp.kind != KV_V) ext_k_img = img;  // KV_K or KV_KV span
+                    if (sp.kind == KV_K) { ext_k_slot = (int)slot; }
+                    if (sp.last_of_layer) {
+                        char *vimg = sp.kind == KV_KV ? img + image : img;
+                        for (int l = 0; l < view->n_layers; ++l) { ext_k[l] = nullptr; ext_v[l] = nullptr; }
+                        ext_k[sp.layer] = ext_k_img;
+                        ext_v[sp.layer] = vimg;
+                        kv_view_t ev = *view;
+                        ev.layout = KV_LAYOUT_BHSD;
+                        ev.k_layers = ext_k.data();
+                        ev.v_layers = ext_v.data();
+                        ev.layer_bytes = image;
+                        ev.stride_b = (int64_t)p->H * p->D;
+                        ev.stride_h = p->D;
+                        ev.stride_s = (int64_t)p->B * p->H * p->D;
+                        ev.s_alloc = p->cap[0];
+                        time_begin(KV_KERNEL_ATTN_PARTIAL);
+                        err = kv_decode_attn(p, &ev, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
+                                             attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
+                        time_end();
+                        if (err != KV_OK) break;
+                        if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
+                        KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_compute));
+                        if (sp.kind == KV_V && ext_k_slot >= 0) KV_HIP_BRK(hipEventRecord(q->ev_free[ext_k_slot], q->s_compute));
+                    }
                 }
                 if (serialize) KV_HIP_BRK(hipStreamSynchronize(q->s_compute));
             }

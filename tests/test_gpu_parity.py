@@ -323,6 +323,33 @@ def test_pipeline_reload_attention(case, span_chunks):
     _check_restored(case, k_new, v_new, range(cfg.n_layers))
 
 
+def test_pipeline_reload_attention_from_extent(case):
+    """Decode attention fed straight from the staged extent images (no unpack): same outputs, and the
+    destination view is neither read nor written."""
+    cfg, r = case.cfg, case.ref
+    if r.per_seq:
+        pytest.skip("token-major extents only")
+    region = pinned_bytes(r.region_bytes, 0)
+    arena = np.zeros(max(r.pageable_bytes, 1), dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=cfg.depth)
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    qs = [W.query(cfg, l, "cpu") for l in range(cfg.n_layers)]
+    qd = [q.cuda() for q in qs]
+    outs = [torch.full((len(case.lens), cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+            for _ in range(cfg.n_layers)]
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, view, region, arena,
+                            depth=cfg.depth, q_layers=qd, out_layers=outs, attn_from_extent=True)
+    assert st.kernel_launches[kv.KV_KERNEL_UNPACK] == 0
+    assert st.kernel_launches[kv.KV_KERNEL_ATTN_PARTIAL] == cfg.n_layers
+    for l in range(cfg.n_layers):
+        _attn_check(outs[l], case.expected_attention(l, qs[l]))
+        assert (bits(k_new[l]) == 0x7E7E).all() and (bits(v_new[l]) == 0x7E7E).all()
+    with pytest.raises(kv.KVError):
+        kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, view, region, arena, depth=cfg.depth,
+                           q_layers=qd, out_layers=outs, attn_from_extent=True, span_chunks=1)
+
+
 def test_pipeline_layer_subrange_and_other_chunk_size(case):
     """Only the requested layers move; a different (aligned) chunk size gives the same bytes."""
     cfg, r = case.cfg, case.ref
