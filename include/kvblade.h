@@ -301,6 +301,45 @@ int kv_pipeline_run(kv_plan_t *plan, int dir, int layer_begin, int layer_end, co
                     int chunk_tokens, int depth, const kv_attn_args_t *attn, const kv_pipe_opts_t *opts,
                     kv_pipe_stats_t *stats);
 
+/*
+ * kv_append_tokens -- decode append (Sec. II-A: after each decode step the newly generated KV pair is
+ * stored back; Sec. III: the 256 KB-class decode write).  For every tensor of layers
+ * [layer_begin, layer_end) and every sequence b, token row len_b - 1 of the view (len_b =
+ * view->seq_lens_host[b], which already counts the new token; 1 <= len_b <= capacity; uniform in
+ * token-major mode) is packed on the GPU and written to its place in the extent: Alg. 2 with
+ * i0 = len_b - 1 gives the byte range, the write carries the whole sectors that contain it.  A row that
+ * starts inside a sector is merged with the sector's earlier bytes: the first append after an offload
+ * reads that sector back (counted in n_rmw_reads), later appends use the image the library keeps;
+ * bytes after the row up to the sector end are written as zeros (no later row exists yet).
+ * Blocking.  lba_region / pageable as in kv_pipeline_run (pinned-ness is not required here).
+ * kv_pipeline_run(KV_DIR_OFFLOAD) forgets the kept sector images.
+ */
+typedef struct kv_append_stats {
+    uint32_t n_cmds;         /* write commands (one per tensor and sequence) */
+    uint32_t n_rmw_reads;    /* sectors read back for read-modify-write */
+    uint64_t blocks_written; /* sectors written */
+} kv_append_stats_t;
+int kv_append_tokens(kv_plan_t *plan, int layer_begin, int layer_end, const kv_view_t *view, void *lba_region,
+                     size_t region_bytes, void *pageable, size_t pageable_bytes, kv_append_stats_t *stats);
+
+/*
+ * kv_budget -- Eq. 1-2, the page-cache budget the knob X of kv_layout_plan is drawn from:
+ * M* = min(M_avail, M_max - M_anon+shmem), B_pc = max(0, M* - N_threads * M_pin).  All in bytes, signed
+ * (an over-committed limit gives a negative M* and B_pc = 0).  The caller samples the memory figures.
+ */
+int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, int32_t n_threads, int64_t m_pin,
+              int64_t *m_star, int64_t *b_pc);
+
+/*
+ * kv_plan_trim -- context teardown (Sec. IV-B "Dataset Management--Deallocate"): for every tensor of
+ * layers [layer_begin, layer_end) the range <lba_start, n_blocks> of the map M is given back.  In the
+ * host-memory model a deallocated block reads back as zeros: the extent bytes in lba_region (direct
+ * path) or pageable (page-cache path) are cleared.  *n_ranges, *n_blocks (nullable) count the ranges
+ * and sectors released.  KV_ENOSPC if a buffer does not cover an extent; nothing is written then.
+ */
+int kv_plan_trim(const kv_plan_t *plan, int layer_begin, int layer_end, void *lba_region, size_t region_bytes,
+                 void *pageable, size_t pageable_bytes, uint64_t *n_ranges, uint64_t *n_blocks);
+
 /* ------------------------------------------------------------------------------------------ */
 int kv_last_hip_error(void);       /* hipError_t of the last KV_EHIP on this thread, else 0 */
 const char *kv_strerror(int code); /* static string */

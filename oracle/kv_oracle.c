@@ -48,6 +48,30 @@ int64_t orc_residency(uint64_t X, uint64_t S_kpu, int64_t L, int32_t *x /* [L] *
     return n1;
 }
 
+/*
+ * Eq. 1-2: page-cache budget.  M* = min(M_avail, M_max - M_anon+shmem);
+ * B_pc = max(0, M* - N_threads * M_pin).  Signed 64-bit so that an over-committed cgroup
+ * (M_anon+shmem > M_max) gives a negative M* and a zero budget.
+ */
+void orc_budget(int64_t M_avail, int64_t M_max, int64_t M_anon_shmem, int64_t N_threads, int64_t M_pin,
+                int64_t *M_star, int64_t *B_pc)
+{
+    int64_t limit = M_max - M_anon_shmem;
+    *M_star = M_avail < limit ? M_avail : limit;
+    int64_t b = *M_star - N_threads * M_pin;
+    *B_pc = b > 0 ? b : 0;
+}
+
+/*
+ * Dataset-management deallocate (Sec. IV-B "TRIM"): for tensor n, the range <lba_start, n_blocks> of M
+ * no longer holds valid data.  In the host-memory model a deallocated block reads back as zeros.
+ * buf is the tensor's host buffer (region or arena), off the byte offset of its extent.
+ */
+void orc_trim(uint8_t *buf, uint64_t off, uint64_t n_blocks, uint64_t lba_size)
+{
+    memset(buf + off, 0, n_blocks * lba_size);
+}
+
 /* Blocks of one sequence's rows: ceil(cap * row_bytes / lba_size). */
 static uint64_t blocks_of(uint64_t bytes, uint64_t lba_size)
 {

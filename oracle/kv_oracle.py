@@ -67,6 +67,10 @@ def lib():
         _lib.orc_attention.restype = C.c_int
         _lib.orc_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int64,
                                        C.c_int64, C.c_void_p, C.c_void_p]
+        _lib.orc_budget.restype = None
+        _lib.orc_budget.argtypes = [C.c_int64] * 5 + [C.c_void_p, C.c_void_p]
+        _lib.orc_trim.restype = None
+        _lib.orc_trim.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64]
         _lib.orc_f16_to_double.restype = C.c_double
         _lib.orc_f16_to_double.argtypes = [C.c_uint16]
         _lib.orc_bf16_to_double.restype = C.c_double
@@ -79,6 +83,18 @@ def _p(a: np.ndarray):
 
 
 # ---------------------------------------------------------------- plan pieces
+def budget(M_avail: int, M_max: int, M_anon_shmem: int, N_threads: int, M_pin: int):
+    """Eq. 1-2.  Returns (M_star, B_pc)."""
+    a, b = C.c_int64(), C.c_int64()
+    lib().orc_budget(M_avail, M_max, M_anon_shmem, N_threads, M_pin, C.byref(a), C.byref(b))
+    return int(a.value), int(b.value)
+
+
+def trim(buf: np.ndarray, off: int, n_blocks: int, lba_size: int) -> None:
+    assert buf.dtype == np.uint8 and off + n_blocks * lba_size <= buf.size
+    lib().orc_trim(_p(buf), off, n_blocks, lba_size)
+
+
 def residency(X: int, S_kpu: int, L: int):
     x = np.zeros(L, dtype=np.int32)
     n1 = lib().orc_residency(X, S_kpu, L, _p(x))

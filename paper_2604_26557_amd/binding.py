@@ -34,6 +34,7 @@ EXPORTS = [
     "kv_layout_plan", "kv_plan_destroy", "kv_plan_info", "kv_plan_tensor", "kv_plan_seq_base",
     "kv_plan_translate", "kv_plan_chunk_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
+    "kv_append_tokens", "kv_budget", "kv_plan_trim",
 ]
 
 
@@ -91,6 +92,10 @@ class kv_pipe_stats_t(C.Structure):
                 ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4)]
 
 
+class kv_append_stats_t(C.Structure):
+    _fields_ = [("n_cmds", C.c_uint32), ("n_rmw_reads", C.c_uint32), ("blocks_written", C.c_uint64)]
+
+
 _lib = None
 
 
@@ -122,6 +127,12 @@ def lib() -> C.CDLL:
         L.kv_pipeline_run.argtypes = [vp, i, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t, i, i,
                                       C.POINTER(kv_attn_args_t), C.POINTER(kv_pipe_opts_t),
                                       C.POINTER(kv_pipe_stats_t)]
+        L.kv_append_tokens.argtypes = [vp, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t,
+                                       C.POINTER(kv_append_stats_t)]
+        L.kv_budget.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.POINTER(C.c_int64),
+                                C.POINTER(C.c_int64)]
+        L.kv_plan_trim.argtypes = [vp, i, i, vp, C.c_size_t, vp, C.c_size_t, C.POINTER(C.c_uint64),
+                                   C.POINTER(C.c_uint64)]
         L.kv_strerror.restype = C.c_char_p
         L.kv_strerror.argtypes = [i]
         for name in EXPORTS:
@@ -334,3 +345,36 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
     del keep
     _check(rc, "kv_pipeline_run")
     return st
+
+
+def _host_buf(buf):
+    if buf is None:
+        return None, 0
+    if isinstance(buf, np.ndarray):
+        return buf.ctypes.data, buf.nbytes
+    return buf.data_ptr(), buf.numel() * buf.element_size()
+
+
+def kv_append_tokens(plan: Plan, layer_begin: int, layer_end: int, view: View, lba_region=None,
+                     pageable=None) -> kv_append_stats_t:
+    rp, rb = _host_buf(lba_region)
+    pp, pb = _host_buf(pageable)
+    st = kv_append_stats_t()
+    _check(lib().kv_append_tokens(plan.handle, layer_begin, layer_end, view.ref(), rp, rb, pp, pb, C.byref(st)),
+           "kv_append_tokens")
+    return st
+
+
+def kv_budget(m_avail: int, m_max: int, m_anon_shmem: int, n_threads: int, m_pin: int):
+    a, b = C.c_int64(), C.c_int64()
+    _check(lib().kv_budget(m_avail, m_max, m_anon_shmem, n_threads, m_pin, C.byref(a), C.byref(b)), "kv_budget")
+    return int(a.value), int(b.value)
+
+
+def kv_plan_trim(plan: Plan, layer_begin: int, layer_end: int, lba_region=None, pageable=None):
+    rp, rb = _host_buf(lba_region)
+    pp, pb = _host_buf(pageable)
+    n, k = C.c_uint64(), C.c_uint64()
+    _check(lib().kv_plan_trim(plan.handle, layer_begin, layer_end, rp, rb, pp, pb, C.byref(n), C.byref(k)),
+           "kv_plan_trim")
+    return int(n.value), int(k.value)

@@ -330,6 +330,27 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
 }  // namespace
 
 namespace kvb {
+// Token rows [tok0, tok0+ntok) of sequence b (every sequence's in token-major mode: b = -1) of tensor
+// (layer, kind) in extent order at dst, with no sector alignment rule and no padding.  Used by the
+// decode append, whose single rows may start and end inside a sector.
+int pack_rows_raw(const kv_plan *p, const kv_view_t *v, int layer, int kind, int b, int tok0, int ntok, void *dst,
+                  size_t dst_bytes, hipStream_t stream)
+{
+    if (!p || !dst || ((uintptr_t)dst & 15)) return KV_EINVAL;
+    if (kind != KV_K && kind != KV_V) return KV_EINVAL;
+    int rc = check_view(p, v, layer);
+    if (rc != KV_OK) return rc;
+    if (tok0 < 0 || ntok <= 0) return KV_EINVAL;
+    if (p->mode == KV_TOKEN_MAJOR ? b != -1 : (b < 0 || b >= p->B)) return KV_ERANGE;
+    if ((uint64_t)tok0 + (uint64_t)ntok > (uint64_t)p->cap[b < 0 ? 0 : b]) return KV_ERANGE;
+    if (dst_bytes < (uint64_t)ntok * p->row_bytes) return KV_ENOSPC;
+    rc = check_rows(p, v, b, tok0, ntok);
+    if (rc != KV_OK) return rc;
+    Seg s{};
+    s.img_off = 0; s.b = b; s.tok0 = tok0; s.ntok = ntok; s.which = kind;
+    return launch<true>(p, v, layer, &s, 1, dst, stream);
+}
+
 // Measurement hook (not part of the C ABI): launch shape of the pack / unpack kernels.
 void set_layout_tuning(int tile_bytes, int unroll, bool nt_load, bool nt_store)
 {

@@ -183,6 +183,12 @@ struct kv_pipeline {
     std::vector<Entry> ring;                    // per in-flight command
     std::vector<hipEvent_t> timing;             // pairs
     Workers workers;
+    // decode append: pinned landing buffer for the packed rows, and per (tensor, sequence) the image of
+    // the last partly filled sector (so that only the first append after an offload has to read it back)
+    void *append_host = nullptr;
+    size_t append_host_bytes = 0;
+    std::vector<char> tail_img;
+    std::vector<int64_t> tail_sector;
 
     ~kv_pipeline()
     {
@@ -197,6 +203,7 @@ struct kv_pipeline {
         for (auto e : timing) (void)hipEventDestroy(e);
         if (staging) (void)hipFree(staging);
         if (bounce) (void)hipHostFree(bounce);
+        if (append_host) (void)hipHostFree(append_host);
         if (attn_ws) (void)hipFree(attn_ws);
         for (auto st : s_copy) if (st) (void)hipStreamDestroy(st);
         if (s_compute) (void)hipStreamDestroy(s_compute);
@@ -423,6 +430,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     };
 
     const bool offload = offload_dir;
+    if (offload) std::fill(q->tail_sector.begin(), q->tail_sector.end(), (int64_t)-1);  // extents are rewritten
     const size_t N = chunks.size();
     std::vector<unsigned> slot_used(n_slots, 0u);  // copy streams that carried the slot's last span
     size_t n_waited = 0;  // chunks [0, n_waited) are known complete
@@ -656,4 +664,94 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         stats->wall_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
     }
     return err;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Decode append.
+extern "C" int kv_append_tokens(kv_plan_t *p, int layer_begin, int layer_end, const kv_view_t *view, void *lba_region,
+                                size_t region_bytes, void *pageable, size_t pageable_bytes, kv_append_stats_t *stats)
+{
+    if (!p || !view || !view->seq_lens_host) return KV_EINVAL;
+    if (layer_begin < 0 || layer_end > p->L || layer_begin > layer_end || layer_end > view->n_layers) return KV_ERANGE;
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    if (layer_begin == layer_end) return KV_OK;
+    const uint64_t sec = (uint64_t)p->sector, rb = p->row_bytes;
+    const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
+    for (int b = 0; b < p->B; ++b) {
+        const int len = view->seq_lens_host[b];
+        if (len < 1 || len > p->cap[b]) return KV_ERANGE;
+        if (p->mode == KV_TOKEN_MAJOR && len != view->seq_lens_host[0]) return KV_EINVAL;
+    }
+    bool any_direct = false, any_pc = false;
+    for (int l = layer_begin; l < layer_end; ++l) (l < p->n1 ? any_pc : any_direct) = true;
+    if (any_direct && (!lba_region || region_bytes < p->region_bytes_needed)) return lba_region ? KV_ENOSPC : KV_EINVAL;
+    if (any_pc && (!pageable || pageable_bytes < p->pageable_bytes_needed)) return pageable ? KV_ENOSPC : KV_EINVAL;
+
+    const size_t n_rows = (size_t)(layer_end - layer_begin) * 2 * (size_t)nseq;
+    const size_t total = n_rows * rb;
+    int rc = ensure_pipeline(p, 1, kvb::round_up(total, 4096), 1, 0, false, 0, 0, 0);
+    if (rc != KV_OK) return rc;
+    kv_pipeline *q = p->pipe;
+    if (q->append_host_bytes < total) {
+        if (q->append_host) KV_HIP(hipHostFree(q->append_host));
+        q->append_host = nullptr; q->append_host_bytes = 0;
+        KV_HIP(hipHostMalloc(&q->append_host, total, hipHostMallocDefault));
+        q->append_host_bytes = total;
+    }
+    const size_t n_entries = (size_t)p->L * 2 * (size_t)nseq;
+    if (q->tail_sector.size() != n_entries) {
+        q->tail_sector.assign(n_entries, -1);
+        q->tail_img.assign(n_entries * sec, 0);
+    }
+
+    // GPU side: the new row of every tensor (and sequence) in extent order, then one transfer
+    size_t idx = 0;
+    for (int l = layer_begin; l < layer_end; ++l)
+        for (int kind = 0; kind < 2; ++kind)
+            for (int b = 0; b < nseq; ++b, ++idx) {
+                const int len = view->seq_lens_host[b];
+                rc = kvb::pack_rows_raw(p, view, l, kind, p->mode == KV_TOKEN_MAJOR ? -1 : b, len - 1, 1,
+                                        (char *)q->staging + idx * rb, rb, q->s_compute);
+                if (rc != KV_OK) { (void)hipStreamSynchronize(q->s_compute); return rc; }
+            }
+    KV_HIP(hipMemcpyAsync(q->append_host, q->staging, total, hipMemcpyDeviceToHost, q->s_compute));
+    KV_HIP(hipStreamSynchronize(q->s_compute));
+
+    // Host side: Alg. 2 with i0 = len-1 gives the row's byte range; the write command carries whole
+    // sectors, so a row that starts inside a sector is merged with that sector's earlier bytes
+    // (read-modify-write; the sector image is kept for the next append) and the rest is zeros.
+    std::vector<char> tmp;
+    idx = 0;
+    for (int l = layer_begin; l < layer_end; ++l)
+        for (int kind = 0; kind < 2; ++kind)
+            for (int b = 0; b < nseq; ++b, ++idx) {
+                const int n = 2 * l + kind;
+                const bool direct = p->ext[n].path == KV_PATH_DIRECT;
+                const uint64_t a = (uint64_t)(view->seq_lens_host[b] - 1) * rb, e = a + rb;
+                const uint64_t sec0 = a / sec, sec1 = kvb::ceil_div(e, sec), nsec = sec1 - sec0;
+                const uint64_t off = kvb::extent_host_off(p, n) + p->seq_base[b] * sec + sec0 * sec;
+                if (off + nsec * sec > (direct ? region_bytes : pageable_bytes)) return KV_ENOSPC;
+                char *host = (char *)(direct ? lba_region : pageable) + off;
+                const size_t entry = ((size_t)n * nseq) + (size_t)b;
+                tmp.assign(nsec * sec, 0);
+                const uint64_t head = a - sec0 * sec;
+                if (head > 0) {
+                    if (q->tail_sector[entry] == (int64_t)sec0) {
+                        std::memcpy(tmp.data(), q->tail_img.data() + entry * sec, head);
+                    } else {
+                        std::memcpy(tmp.data(), host, head);  // the read of the read-modify-write
+                        if (stats) stats->n_rmw_reads++;
+                    }
+                }
+                std::memcpy(tmp.data() + head, (char *)q->append_host + idx * rb, rb);
+                std::memcpy(host, tmp.data(), nsec * sec);    // write command: nlb = nsec - 1
+                if (e % sec != 0) {
+                    std::memcpy(q->tail_img.data() + entry * sec, tmp.data() + (nsec - 1) * sec, sec);
+                    q->tail_sector[entry] = (int64_t)(sec1 - 1);
+                } else {
+                    q->tail_sector[entry] = -1;
+                }
+                if (stats) { stats->n_cmds++; stats->blocks_written += nsec; }
+            }
+    return KV_OK;
 }

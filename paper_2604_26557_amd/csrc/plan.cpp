@@ -3,6 +3,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <cstring>
 #include <new>
 
 namespace kvb {
@@ -222,6 +223,48 @@ extern "C" int kv_plan_chunk_cmds(const kv_plan_t *p, int layer, int kind, int s
     if (rc != KV_OK) return rc;
     *n = (int)v.size();
     for (int i = 0; i < (int)v.size() && i < cap; ++i) out[i] = v[i];
+    return KV_OK;
+}
+
+extern "C" int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, int32_t n_threads, int64_t m_pin,
+                         int64_t *m_star, int64_t *b_pc)
+{
+    if (!m_star || !b_pc || n_threads < 0 || m_pin < 0) return KV_EINVAL;
+    const int64_t limit = m_max - m_anon_shmem;           // Eq. 1
+    *m_star = std::min(m_avail, limit);
+    const int64_t left = *m_star - (int64_t)n_threads * m_pin;  // Eq. 2
+    *b_pc = std::max<int64_t>(0, left);
+    return KV_OK;
+}
+
+extern "C" int kv_plan_trim(const kv_plan_t *p, int layer_begin, int layer_end, void *lba_region, size_t region_bytes,
+                            void *pageable, size_t pageable_bytes, uint64_t *n_ranges, uint64_t *n_blocks)
+{
+    if (!p) return KV_EINVAL;
+    if (layer_begin < 0 || layer_end > p->L || layer_begin > layer_end) return KV_ERANGE;
+    const uint64_t sec = (uint64_t)p->sector;
+    uint64_t ranges = 0, blocks = 0;
+    for (int pass = 0; pass < 2; ++pass) {  // validate everything first, then write
+        for (int l = layer_begin; l < layer_end; ++l) {
+            for (int kind = 0; kind < 2; ++kind) {
+                const kv_extent_t &e = p->ext[2 * l + kind];      // the entry of M (Eq. 3-4)
+                const bool direct = e.path == KV_PATH_DIRECT;
+                char *base = (char *)(direct ? lba_region : pageable);
+                const uint64_t cap = direct ? region_bytes : pageable_bytes;
+                const uint64_t off = extent_host_off(p, 2 * l + kind);
+                if (pass == 0) {
+                    if (!base) return KV_EINVAL;
+                    if (off + e.n_blocks * sec > cap) return KV_ENOSPC;
+                } else {
+                    std::memset(base + off, 0, e.n_blocks * sec);  // a deallocated block reads back as zeros
+                    ++ranges;
+                    blocks += e.n_blocks;
+                }
+            }
+        }
+    }
+    if (n_ranges) *n_ranges = ranges;
+    if (n_blocks) *n_blocks = blocks;
     return KV_OK;
 }
 

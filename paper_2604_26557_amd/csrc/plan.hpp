@@ -2,6 +2,8 @@
 // planner accessors, the kernel launchers and the pipeline.
 #pragma once
 
+#include <hip/hip_runtime_api.h>
+
 #include <cstdint>
 #include <vector>
 
@@ -53,5 +55,9 @@ inline uint64_t extent_host_off(const kv_plan *p, int n)
 int chunk_cmds(const kv_plan *p, int layer, int kind, int seq, int chunk_tokens, std::vector<kv_cmd_t> *out);
 
 void set_hip_error(int e);
+
+// layout_kernels.hip
+int pack_rows_raw(const kv_plan *p, const kv_view_t *v, int layer, int kind, int b, int tok0, int ntok, void *dst,
+                  size_t dst_bytes, hipStream_t stream);
 
 }  // namespace kvb

@@ -29,23 +29,25 @@ class Case:
     sides see the same bits whichever generator produced them."""
 
     def __init__(self, cfg: W.KVConfig, device: str = "cuda", raw: bool = False, gen_device: Optional[str] = None,
-                 keep_cpu: bool = True, s_extra: int = 0, lens: Optional[List[int]] = None):
+                 keep_cpu: bool = True, s_extra: int = 0, lens: Optional[List[int]] = None, cap_extra: int = 0):
         self.cfg = cfg
         self.device = device
         self.lens = W.seq_lens(cfg) if lens is None else lens
-        self.plan = native_plan(cfg, self.lens)
-        self.ref = oracle_plan(cfg, self.lens)
+        # extents (and the source buffers) may hold cap_extra more tokens than are valid (decode appends)
+        self.caps = [n + cap_extra for n in self.lens]
+        self.plan = native_plan(cfg, self.caps)
+        self.ref = oracle_plan(cfg, self.caps)
         gd = device if gen_device is None else gen_device
         L = cfg.n_layers
         self.paged = cfg.layout == W.PAGED
         if self.paged:
-            table, n_pool = W.block_table(cfg, self.lens)
+            table, n_pool = W.block_table(cfg, self.caps)
             self.table_cpu = table
             self.table_dev = table.to(device)
             self.n_pool = n_pool
             mk = lambda l, k: W.paged_layer(cfg, l, k, n_pool, gd, raw=raw).to(device)
         else:
-            s_alloc = max(self.lens) + s_extra
+            s_alloc = max(self.caps) + s_extra
             mk = lambda l, k: W.bhsd_layer(cfg, l, k, gd, raw=raw, s_alloc=s_alloc).to(device)
         self.k = [mk(l, 0) for l in range(L)]
         self.v = [mk(l, 1) for l in range(L)]
@@ -55,10 +57,12 @@ class Case:
         self.view = self.make_view(self.k, self.v)
 
     # ---- native side
-    def make_view(self, k, v) -> kv.View:
+    def make_view(self, k, v, lens: Optional[List[int]] = None) -> kv.View:
+        lens_dev = self.lens_dev if lens is None else torch.tensor(lens, dtype=torch.int32, device=self.device)
+        lens = self.lens if lens is None else lens
         if self.paged:
-            return kv.paged_view(k, v, self.table_dev, self.lens, self.lens_dev)
-        return kv.bhsd_view(k, v, self.lens, self.lens_dev)
+            return kv.paged_view(k, v, self.table_dev, lens, lens_dev)
+        return kv.bhsd_view(k, v, lens, lens_dev)
 
     def blank_like_source(self, fill: int = 0x7E7E):
         """Fresh device tensors shaped like the source, filled with a 16-bit pattern."""
@@ -78,15 +82,17 @@ class Case:
     def tensor_cpu(self, layer: int, kind: int) -> torch.Tensor:
         return (self.k_cpu if kind == 0 else self.v_cpu)[layer]
 
-    def expected_extent(self, layer: int, kind: int, t_cpu: Optional[torch.Tensor] = None) -> np.ndarray:
+    def expected_extent(self, layer: int, kind: int, t_cpu: Optional[torch.Tensor] = None,
+                        lens: Optional[List[int]] = None) -> np.ndarray:
         """The whole extent image of one tensor (payload + zero pad) by the checker."""
         r = self.ref
         t = self.tensor_cpu(layer, kind) if t_cpu is None else t_cpu
         ext = np.full(r.n_blocks_tensor * r.lba_size, 0xEE, dtype=np.uint8)
-        o.pack(self.source(t), o.u16(t), r.per_seq, self.lens, r.seq_base, r.n_blocks_tensor, r.lba_size, ext)
+        o.pack(self.source(t), o.u16(t), r.per_seq, self.lens if lens is None else lens, r.seq_base,
+               r.n_blocks_tensor, r.lba_size, ext)
         return ext
 
-    def expected_host(self, layers=None, fill: int = 0xC3):
+    def expected_host(self, layers=None, fill: int = 0xC3, lens: Optional[List[int]] = None):
         """(region, arena) images after offloading `layers` (default all) into buffers pre-filled with `fill`."""
         r = self.ref
         region = np.full(max(r.region_bytes, 1), fill, dtype=np.uint8)
@@ -96,7 +102,7 @@ class Case:
                 n = 2 * layer + kind
                 buf = region if r.path[n] == 0 else arena
                 off = r.ext_byte_off(n)
-                buf[off:off + r.n_blocks_tensor * r.lba_size] = self.expected_extent(layer, kind)
+                buf[off:off + r.n_blocks_tensor * r.lba_size] = self.expected_extent(layer, kind, lens=lens)
         return region, arena
 
     def expected_attention(self, layer: int, q_cpu: torch.Tensor) -> np.ndarray:

@@ -391,3 +391,52 @@ def test_pipeline_argument_errors(case):
         assert code(pageable=arena[:r.pageable_bytes - 1]) == kv.KV_ENOSPC
     if r.row_bytes % r.lba_size:
         assert code(chunk_tokens=1) == kv.KV_EALIGN
+
+
+# ------------------------------------------------------------------------------------------ decode append
+APPEND_CONFIGS = [
+    SMALL[0],                                                    # 256 B rows in 512 B sectors: two rows per sector
+    SMALL[5],                                                    # 1920 B rows in 512 B sectors: unaligned, 4-5 sectors
+    W.shrink(SMALL[4], seq_len=100, pc_budget_bytes=2 * 103 * 32768),   # 32 KiB rows, 4 KiB sectors: aligned, no merge
+    W.shrink(SMALL[3], len_range=(33, 200)),                     # ragged, paged, per-sequence extents, 2 KiB rows
+    W.shrink(SMALL[2], seq_len=301, pc_budget_bytes=4 * 304 * 2048),    # both paths, odd length: first append merges
+]
+
+
+@pytest.mark.parametrize("cfg", APPEND_CONFIGS, ids=lambda c: c.name)
+def test_decode_append(cfg):
+    """Offload len tokens, then append three tokens one by one; after each the host bytes must equal the
+    checker's pack of the longer cache.  Only the first append after the offload may read a sector back."""
+    EXTRA = 3
+    case = Case(cfg, "cuda", gen_device="cpu", cap_extra=EXTRA)
+    r = case.ref
+    FILL = 0x99
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=2)
+    lens = list(case.lens)
+    row, sec = r.row_bytes, r.lba_size
+    for step in range(EXTRA):
+        lens = [n + 1 for n in lens]
+        view = case.make_view(case.k, case.v, lens)
+        st = kv.kv_append_tokens(case.plan, 0, cfg.n_layers, view, region, arena)
+        want_region, want_arena = case.expected_host(fill=FILL, lens=lens)
+        assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes]), step
+        assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes]), step
+        nseq = len(lens) if r.per_seq else 1
+        assert st.n_cmds == 2 * cfg.n_layers * nseq
+        starts_inside = sum(((n - 1) * row) % sec != 0 for n in lens[:nseq])
+        assert st.n_rmw_reads == (2 * cfg.n_layers * starts_inside if step == 0 else 0)
+    # attention over the longer cache includes the appended tokens
+    q = W.query(cfg, 0, "cpu")
+    out = torch.empty((len(lens), cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+    ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, 0, max(lens)), dtype=torch.uint8, device="cuda")
+    kv.kv_decode_attn(case.plan, view, 0, q.cuda(), out, kv.KV_OUT_F32, 0, ws)
+    torch.cuda.synchronize()
+    K, V = case.k_cpu[0], case.v_cpu[0]
+    want = o.attention(case.source(K), o.u16(K), o.u16(V), o.u16(q), cfg.dtype == W.BF16, lens, cfg.n_q_heads)
+    _attn_check(out, want)
+    # capacity is a hard bound
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_append_tokens(case.plan, 0, cfg.n_layers, case.make_view(case.k, case.v, [n + 1 for n in lens]), region, arena)
+    assert e.value.code == kv.KV_ERANGE

@@ -233,3 +233,22 @@ def test_token_range_helper_matches_alg2():
             assert rc == o.OK
             assert slba == int(p.lba_start[n]) + int(p.seq_base[b]) + 4 * 256 // 512
             assert req == 8 * 256
+
+
+# ------------------------------------------------------------------ Eq. 1-2
+def test_budget_closed_forms():
+    GB = 10**9
+    pin = 128 * MiB                                            # one K or V tensor at the paper's shape
+    assert o.budget(8 * GB, 11 * GB, 2 * GB, 2, pin) == (8 * GB, 8 * GB - 2 * pin)       # M_avail binds
+    assert o.budget(12 * GB, 11 * GB, 2 * GB, 2, pin) == (9 * GB, 9 * GB - 2 * pin)      # the cgroup limit binds
+    assert o.budget(1 * GB, 11 * GB, 2 * GB, 2, GB) == (1 * GB, 0)                        # clamp at zero
+    assert o.budget(5 * GB, 2 * GB, 3 * GB, 2, pin) == (-1 * GB, 0)                       # over-committed cgroup
+    assert o.budget(4 * GB, 4 * GB, 0, 0, pin) == (4 * GB, 4 * GB)                        # no copy threads
+    for t in range(5):                                                                    # each thread costs M_pin
+        assert o.budget(4 * GB, 9 * GB, 0, t, pin)[1] == 4 * GB - t * pin
+
+
+def test_trim_zeroes_exactly_the_extent():
+    buf = np.full(10 * 512, 0xAB, dtype=np.uint8)
+    o.trim(buf, 3 * 512, 4, 512)
+    assert (buf[:3 * 512] == 0xAB).all() and not buf[3 * 512:7 * 512].any() and (buf[7 * 512:] == 0xAB).all()

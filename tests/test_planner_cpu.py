@@ -168,3 +168,32 @@ def test_odd_tail_rounds_up():
     assert slba == 2048 + 2049 + 2048 and req == 4096
     cmds = kv.kv_plan_chunk_cmds(p, 0, 0, 0)
     assert len(cmds) == 17 and cmds[-1].nlb == 0 and cmds[-1].ntok == 1
+
+
+def test_budget_matches_oracle():
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        a, m, s = (int(x) for x in rng.integers(0, 20 * 10**9, 3))
+        t, pin = int(rng.integers(0, 5)), int(rng.integers(0, 10**9))
+        assert kv.kv_budget(a, m, s, t, pin) == o.budget(a, m, s, t, pin)
+    assert kv.kv_budget(8 * 10**9, 11 * 10**9, 2 * 10**9, 2, 128 * W.MiB) == (8 * 10**9, 8 * 10**9 - 256 * W.MiB)
+    with pytest.raises(kv.KVError):
+        kv.kv_budget(1, 1, 0, -1, 1)
+
+
+def test_trim_matches_oracle_and_touches_only_extents():
+    cfg = W.shrink(W.CONFIGS[2], n_layers=4, seq_len=100, chunk_tokens=2, pc_budget_bytes=2 * 2 * 100 * 2048)
+    p, ref, lens = _plans(cfg)
+    region = np.full(ref.region_bytes + 4096, 0x5C, dtype=np.uint8)     # one guard sector behind the last extent
+    arena = np.full(ref.pageable_bytes + 4096, 0x5C, dtype=np.uint8)
+    want_r, want_a = region.copy(), arena.copy()
+    for layer in (1, 2):                                                 # layer 1: page-cache path, layer 2: direct
+        for kind in (0, 1):
+            n = 2 * layer + kind
+            o.trim(want_r if ref.path[n] == 0 else want_a, ref.ext_byte_off(n), int(ref.n_blocks[n]), ref.lba_size)
+    assert kv.kv_plan_trim(p, 1, 3, region, arena) == (4, 4 * ref.n_blocks_tensor)
+    assert np.array_equal(region, want_r) and np.array_equal(arena, want_a)
+    assert (region[:2048 * 4096] == 0x5C).all() and (region[-4096:] == 0x5C).all()
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_plan_trim(p, 0, 4, region[:ref.region_bytes - 1], arena)
+    assert e.value.code == kv.KV_ENOSPC
