@@ -161,6 +161,9 @@ typedef struct kv_attn_args {
                                        strided [B,H,S,D] view) and nothing is unpacked: the view's K/V buffers
                                        are neither read nor written */
 
+#define KV_ORDER_CROSS 0 /* per layer all of K's commands, then V's: V's storage-side hop overlaps K's transfers */
+#define KV_ORDER_INTRA 1 /* K's and V's commands alternate: both tensors' storage-side hops run side by side */
+
 typedef struct kv_pipe_opts {
     int32_t span_chunks;  /* chunks of one tensor per kernel launch and staging slot; 0 = a whole layer
                              (K and V in one launch) */
@@ -170,6 +173,8 @@ typedef struct kv_pipe_opts {
                              never more than depth */
     int32_t d2h_mode;     /* KV_COPY_* for offload transfers */
     int32_t h2d_mode;     /* KV_COPY_* for reload transfers */
+    int32_t order_pagecache; /* KV_ORDER_* for page-cache-path layers (the two overlap strategies of Sec. IV-C) */
+    int32_t order_direct;    /* KV_ORDER_* for direct-path layers */
 } kv_pipe_opts_t;
 
 typedef struct kv_pipe_stats {
@@ -179,6 +184,7 @@ typedef struct kv_pipe_stats {
     uint32_t n_chunks;        /* chunk commands issued */
     uint32_t n_spans;         /* staging slots filled */
     uint32_t max_in_flight;   /* largest number of chunk commands outstanding at once */
+    double group_seconds[2];  /* per path group (0 page-cache, 1 direct): first command issued to last harvested */
     uint32_t kernel_launches[4];
     float kernel_ms[4];       /* summed event-bracketed time per kernel kind (KV_PIPE_TIME_KERNELS); the
                                  attention pair is bracketed together and reported under ATTN_PARTIAL */
@@ -339,6 +345,23 @@ int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, int32_t n_th
  */
 int kv_plan_trim(const kv_plan_t *plan, int layer_begin, int layer_end, void *lba_region, size_t region_bytes,
                  void *pageable, size_t pageable_bytes, uint64_t *n_ranges, uint64_t *n_blocks);
+
+/*
+ * Adaptive strategy selection (Sec. IV-C): the first decode iteration is a warm-up and is not measured,
+ * iteration 2 runs KV_ORDER_INTRA, iteration 3 KV_ORDER_CROSS; their throughputs are compared per path
+ * group and the higher one is kept for every later iteration (a tie keeps KV_ORDER_INTRA).  The state is
+ * a plain caller-owned struct.  kv_adapt_order gives the order a group must use in the coming iteration;
+ * kv_adapt_update takes the stats of the iteration that has just run (bytes and group_seconds per group)
+ * and advances the iteration count.  Groups: 0 = page-cache path, 1 = direct path.
+ */
+typedef struct kv_adapt {
+    int32_t iteration;  /* decode iterations completed */
+    int32_t chosen[2];  /* KV_ORDER_* once decided, else -1 */
+    double gbps[2][2];  /* [group][order] throughput measured in iterations 2 and 3 */
+} kv_adapt_t;
+int kv_adapt_init(kv_adapt_t *a);
+int kv_adapt_order(const kv_adapt_t *a, int group);
+int kv_adapt_update(kv_adapt_t *a, const kv_pipe_stats_t *stats);
 
 /* ------------------------------------------------------------------------------------------ */
 int kv_last_hip_error(void);       /* hipError_t of the last KV_EHIP on this thread, else 0 */

@@ -72,6 +72,19 @@ void orc_trim(uint8_t *buf, uint64_t off, uint64_t n_blocks, uint64_t lba_size)
     memset(buf + off, 0, n_blocks * lba_size);
 }
 
+/*
+ * Adaptive strategy selection (Sec. IV-C), per path group.  Decode iterations are counted from 1:
+ * iteration 1 is the warm-up (not measured), iteration 2 runs overlap-intra (code 1), iteration 3
+ * overlap-cross (code 0); from iteration 4 on the strategy with the higher measured throughput is used.
+ * Readings: the warm-up runs overlap-intra; a tie keeps overlap-intra.
+ */
+int orc_adapt_order(int64_t iteration /* 1-based, the one about to run */, double thr_intra, double thr_cross)
+{
+    if (iteration <= 2) return 1;
+    if (iteration == 3) return 0;
+    return thr_cross > thr_intra ? 0 : 1;
+}
+
 /* Blocks of one sequence's rows: ceil(cap * row_bytes / lba_size). */
 static uint64_t blocks_of(uint64_t bytes, uint64_t lba_size)
 {

@@ -71,6 +71,8 @@ def lib():
         _lib.orc_budget.argtypes = [C.c_int64] * 5 + [C.c_void_p, C.c_void_p]
         _lib.orc_trim.restype = None
         _lib.orc_trim.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64]
+        _lib.orc_adapt_order.restype = C.c_int
+        _lib.orc_adapt_order.argtypes = [C.c_int64, C.c_double, C.c_double]
         _lib.orc_f16_to_double.restype = C.c_double
         _lib.orc_f16_to_double.argtypes = [C.c_uint16]
         _lib.orc_bf16_to_double.restype = C.c_double
@@ -93,6 +95,11 @@ def budget(M_avail: int, M_max: int, M_anon_shmem: int, N_threads: int, M_pin: i
 def trim(buf: np.ndarray, off: int, n_blocks: int, lba_size: int) -> None:
     assert buf.dtype == np.uint8 and off + n_blocks * lba_size <= buf.size
     lib().orc_trim(_p(buf), off, n_blocks, lba_size)
+
+
+def adapt_order(iteration: int, thr_intra: float, thr_cross: float) -> int:
+    """Sec. IV-C: strategy (1 = overlap-intra, 0 = overlap-cross) of the 1-based decode iteration about to run."""
+    return int(lib().orc_adapt_order(iteration, thr_intra, thr_cross))
 
 
 def residency(X: int, S_kpu: int, L: int):

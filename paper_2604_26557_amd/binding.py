@@ -29,12 +29,13 @@ KV_PIPE_TIME_KERNELS = 1
 KV_PIPE_SERIALIZE = 2
 KV_PIPE_ATTN_FROM_EXTENT = 4
 KV_COPY_AUTO, KV_COPY_MEMCPY, KV_COPY_KERNEL = 0, 1, 2
+KV_ORDER_CROSS, KV_ORDER_INTRA = 0, 1
 
 EXPORTS = [
     "kv_layout_plan", "kv_plan_destroy", "kv_plan_info", "kv_plan_tensor", "kv_plan_seq_base",
     "kv_plan_translate", "kv_plan_chunk_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
-    "kv_append_tokens", "kv_budget", "kv_plan_trim",
+    "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
 ]
 
 
@@ -83,13 +84,19 @@ class kv_attn_args_t(C.Structure):
 
 class kv_pipe_opts_t(C.Structure):
     _fields_ = [("span_chunks", C.c_int32), ("host_workers", C.c_int32), ("flags", C.c_uint32),
-                ("copy_streams", C.c_int32), ("d2h_mode", C.c_int32), ("h2d_mode", C.c_int32)]
+                ("copy_streams", C.c_int32), ("d2h_mode", C.c_int32), ("h2d_mode", C.c_int32),
+                ("order_pagecache", C.c_int32), ("order_direct", C.c_int32)]
 
 
 class kv_pipe_stats_t(C.Structure):
     _fields_ = [("wall_s", C.c_double), ("bytes_direct", C.c_uint64), ("bytes_pagecache", C.c_uint64),
                 ("n_chunks", C.c_uint32), ("n_spans", C.c_uint32), ("max_in_flight", C.c_uint32),
+                ("group_seconds", C.c_double * 2),
                 ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4)]
+
+
+class kv_adapt_t(C.Structure):
+    _fields_ = [("iteration", C.c_int32), ("chosen", C.c_int32 * 2), ("gbps", (C.c_double * 2) * 2)]
 
 
 class kv_append_stats_t(C.Structure):
@@ -133,6 +140,9 @@ def lib() -> C.CDLL:
                                 C.POINTER(C.c_int64)]
         L.kv_plan_trim.argtypes = [vp, i, i, vp, C.c_size_t, vp, C.c_size_t, C.POINTER(C.c_uint64),
                                    C.POINTER(C.c_uint64)]
+        L.kv_adapt_init.argtypes = [C.POINTER(kv_adapt_t)]
+        L.kv_adapt_order.argtypes = [C.POINTER(kv_adapt_t), i]
+        L.kv_adapt_update.argtypes = [C.POINTER(kv_adapt_t), C.POINTER(kv_pipe_stats_t)]
         L.kv_strerror.restype = C.c_char_p
         L.kv_strerror.argtypes = [i]
         for name in EXPORTS:
@@ -318,7 +328,8 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
                     q_layers=None, out_layers=None, out_dtype: int = KV_OUT_F32, n_splits: int = 0,
                     span_chunks: int = 0, host_workers: int = 0, time_kernels: bool = False,
                     copy_streams: int = 0, d2h_mode: int = KV_COPY_AUTO, h2d_mode: int = KV_COPY_AUTO,
-                    serialize: bool = False, attn_from_extent: bool = False) -> kv_pipe_stats_t:
+                    serialize: bool = False, attn_from_extent: bool = False,
+                    order_pagecache: int = KV_ORDER_CROSS, order_direct: int = KV_ORDER_CROSS) -> kv_pipe_stats_t:
     """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array."""
     def host(buf):
         if buf is None:
@@ -337,7 +348,7 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
         keep = (qa, oa)
     opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0)
                           | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0), copy_streams,
-                          d2h_mode, h2d_mode)
+                          d2h_mode, h2d_mode, order_pagecache, order_direct)
     st = kv_pipe_stats_t()
     rc = lib().kv_pipeline_run(plan.handle, direction, layer_begin, layer_end, view.ref(), rp, rb, pp, pb,
                                chunk_tokens, depth, C.byref(attn) if attn is not None else None, C.byref(opts),
@@ -378,3 +389,20 @@ def kv_plan_trim(plan: Plan, layer_begin: int, layer_end: int, lba_region=None, 
     _check(lib().kv_plan_trim(plan.handle, layer_begin, layer_end, rp, rb, pp, pb, C.byref(n), C.byref(k)),
            "kv_plan_trim")
     return int(n.value), int(k.value)
+
+
+def kv_adapt_init() -> kv_adapt_t:
+    a = kv_adapt_t()
+    _check(lib().kv_adapt_init(C.byref(a)), "kv_adapt_init")
+    return a
+
+
+def kv_adapt_order(a: kv_adapt_t, group: int) -> int:
+    r = lib().kv_adapt_order(C.byref(a), group)
+    if r < 0:
+        raise KVError(r, "kv_adapt_order")
+    return r
+
+
+def kv_adapt_update(a: kv_adapt_t, stats: kv_pipe_stats_t) -> None:
+    _check(lib().kv_adapt_update(C.byref(a), C.byref(stats)), "kv_adapt_update")

@@ -315,6 +315,11 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         return KV_EINVAL;
     const bool d2h_kernel = d2h_mode != KV_COPY_MEMCPY;  // auto: copy kernel
     const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;  // auto: hipMemcpyAsync
+    const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
+    const int order_direct = opts ? opts->order_direct : KV_ORDER_CROSS;
+    if ((order_pc != KV_ORDER_CROSS && order_pc != KV_ORDER_INTRA) ||
+        (order_direct != KV_ORDER_CROSS && order_direct != KV_ORDER_INTRA))
+        return KV_EINVAL;
     if (ns == 0) ns = offload_dir ? 2 : 4;
     ns = std::min(ns, depth);
     if (stats) std::memset(stats, 0, sizeof(*stats));
@@ -355,21 +360,27 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     std::vector<kv_cmd_t> cmds;
     uint64_t slot_bytes = 0;
     const uint64_t image = p->tensor_blocks * sec;
-    // Whole-extent spans: K and V of a layer share one launch while the pair stays within 256 MiB
-    // (measured: pairing gains ~5 % at 64 MiB tensors and loses ~10 % at 256 MiB tensors).
-    const bool pair = span_chunks == 0 && 2 * image <= (256ull << 20);
+    // Units: a span with its chunk commands.  Per layer the K units and the V units are emitted either one
+    // tensor after the other (KV_ORDER_CROSS: V's storage-side hop runs while K's transfers are in flight)
+    // or alternating (KV_ORDER_INTRA: both tensors' hops proceed side by side) -- the two overlap
+    // strategies of Sec. IV-C.
+    struct Unit { Span span; std::vector<Chunk> chunks; };
     for (int l = layer_begin; l < layer_end; ++l) {
-        if (pair) {
-            Span s{l, KV_KV, KV_SEQ_ALL, 0, 0, 2 * image, p->ext[2 * l].path, false};  // V's image after K's
-            spans.push_back(s);
-        }
+        const int order = l < p->n1 ? order_pc : order_direct;
+        // Whole-extent spans: K and V of a layer share one launch while the pair stays within 256 MiB
+        // (measured: pairing gains ~5 % at 64 MiB tensors and loses ~10 % at 256 MiB tensors), or when
+        // their chunks alternate.
+        const bool pair = span_chunks == 0 && (2 * image <= (256ull << 20) || order == KV_ORDER_INTRA);
+        std::vector<Unit> units[2];
         for (int kind = 0; kind < 2; ++kind) {
             const kv_extent_t &ext = p->ext[2 * l + kind];
-            if (span_chunks == 0 && !pair) {
-                Span s{l, kind, KV_SEQ_ALL, 0, 0, image, ext.path, false};
-                spans.push_back(s);
-            }
             const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
+            if (span_chunks == 0) {
+                Unit u;
+                u.span = pair ? Span{l, KV_KV, KV_SEQ_ALL, 0, 0, 2 * image, ext.path, false}
+                              : Span{l, kind, KV_SEQ_ALL, 0, 0, image, ext.path, false};
+                units[kind].push_back(u);
+            }
             for (int b = 0; b < nseq; ++b) {
                 int rc = kvb::chunk_cmds(p, l, kind, b, (int)C, &cmds);
                 if (rc != KV_OK) return rc;
@@ -377,25 +388,59 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                     const kv_cmd_t &c = cmds[i];
                     if (span_chunks > 0 && i % (size_t)span_chunks == 0) {
                         const size_t j = std::min(cmds.size(), i + (size_t)span_chunks) - 1;
-                        Span s{l, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false};
-                        for (size_t k = i; k <= j; ++k) s.bytes += ((uint64_t)cmds[k].nlb + 1) * sec;
-                        spans.push_back(s);
+                        Unit u;
+                        u.span = Span{l, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false};
+                        for (size_t k = i; k <= j; ++k) u.span.bytes += ((uint64_t)cmds[k].nlb + 1) * sec;
+                        units[kind].push_back(u);
                     }
+                    Unit &u = units[kind].back();
                     Chunk ch;
                     ch.host_off = c.slba * sec;
                     ch.bytes = ((uint64_t)c.nlb + 1) * sec;
-                    ch.span = (int)spans.size() - 1;
+                    ch.span = -1;
                     ch.stage_off = span_chunks == 0 ? (pair ? (uint64_t)kind * image : 0) + p->seq_base[b] * sec + c.buf_off
-                                                    : c.buf_off - (uint64_t)spans.back().tok0 * p->row_bytes;
+                                                    : c.buf_off - (uint64_t)u.span.tok0 * p->row_bytes;
                     ch.first = ch.last = false;
                     const uint64_t host_cap = ext.path == KV_PATH_DIRECT ? region_bytes : pageable_bytes;
                     if (ch.host_off + ch.bytes > host_cap) return KV_ENOSPC;
-                    chunks.push_back(ch);
+                    u.chunks.push_back(ch);
                 }
             }
         }
+        auto emit_span = [&](const Span &sp) { spans.push_back(sp); return (int)spans.size() - 1; };
+        auto emit_chunk = [&](Chunk ch, int span) { ch.span = span; chunks.push_back(ch); };
+        if (pair) {
+            // one span; its K commands and V commands in the chosen order
+            const int si = emit_span(units[0][0].span);
+            const std::vector<Chunk> &ck = units[0][0].chunks, &cv = units[1][0].chunks;
+            if (order == KV_ORDER_INTRA) {
+                for (size_t i = 0; i < std::max(ck.size(), cv.size()); ++i) {
+                    if (i < ck.size()) emit_chunk(ck[i], si);
+                    if (i < cv.size()) emit_chunk(cv[i], si);
+                }
+            } else {
+                for (const Chunk &c : ck) emit_chunk(c, si);
+                for (const Chunk &c : cv) emit_chunk(c, si);
+            }
+        } else if (order == KV_ORDER_INTRA) {
+            for (size_t i = 0; i < std::max(units[0].size(), units[1].size()); ++i)
+                for (int kind = 0; kind < 2; ++kind)
+                    if (i < units[kind].size()) {
+                        const int si = emit_span(units[kind][i].span);
+                        for (const Chunk &c : units[kind][i].chunks) emit_chunk(c, si);
+                    }
+        } else {
+            for (int kind = 0; kind < 2; ++kind)
+                for (const Unit &u : units[kind]) {
+                    const int si = emit_span(u.span);
+                    for (const Chunk &c : u.chunks) emit_chunk(c, si);
+                }
+        }
         if (!spans.empty()) spans.back().last_of_layer = true;
     }
+    // last chunk command of each path group (for the per-group throughput figures)
+    long long group_last[2] = {-1, -1};
+    for (size_t i = 0; i < chunks.size(); ++i) group_last[spans[chunks[i].span].path == KV_PATH_PAGECACHE ? 0 : 1] = (long long)i;
     for (size_t i = 0; i < chunks.size(); ++i) {
         chunks[i].first = i == 0 || chunks[i - 1].span != chunks[i].span;
         chunks[i].last = i + 1 == chunks.size() || chunks[i + 1].span != chunks[i].span;
@@ -437,11 +482,20 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     uint32_t max_in_flight = 0;
     int err = KV_OK;
 
+    // Per path group: host time from the issue of its first command to the harvest of its last.
+    double group_t0[2] = {-1.0, -1.0}, group_t1[2] = {-1.0, -1.0};
+    auto now_s = [&]() { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count(); };
+    auto note_issue = [&](size_t c) {
+        const int g = spans[chunks[c].span].path == KV_PATH_PAGECACHE ? 0 : 1;
+        if (group_t0[g] < 0) group_t0[g] = now_s();
+    };
     // Chunk c owns ring entry c % depth from its start until it is known complete.
     auto wait_complete = [&](size_t c) -> int {
         Entry &e = q->ring[c % (size_t)depth];
         KV_HIP(hipEventSynchronize(e.ev));
         spin_until_zero(e.pending);
+        for (int g = 0; g < 2; ++g)
+            if ((long long)c == group_last[g]) group_t1[g] = now_s();
         return KV_OK;
     };
     auto acquire = [&](size_t c) -> int {  // make ring entry of chunk c free
@@ -512,6 +566,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 used = 0;
             }
             if ((err = acquire(c)) != KV_OK) break;
+            note_issue(c);
             Entry &e = q->ring[c % (size_t)depth];
             const int s = (int)(c % (size_t)ns);
             hipStream_t st = q->s_copy[s];
@@ -552,6 +607,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 const bool pc = spans[chunks[cs].span].path == KV_PATH_PAGECACHE;
                 if (cs >= ci + (pc ? look : 1)) break;
                 if ((err = acquire(cs)) != KV_OK) break;
+                note_issue(cs);
                 Entry &e = q->ring[cs % (size_t)depth];
                 if (pc) fan_out(cs, bounce_ptr(cs), host_ptr(chunks[cs]), chunks[cs].bytes, nullptr);
                 else e.pending.store(0, std::memory_order_release);
@@ -652,7 +708,11 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         kvb::set_hip_error((int)(e1 != hipSuccess ? e1 : e2));
         err = KV_EHIP;
     }
+    for (int g = 0; g < 2; ++g)
+        if (group_t0[g] >= 0 && group_t1[g] < 0) group_t1[g] = now_s();  // harvested by the drain
     if (stats) {
+        stats->group_seconds[0] = group_t0[0] >= 0 ? group_t1[0] - group_t0[0] : 0.0;
+        stats->group_seconds[1] = group_t0[1] >= 0 ? group_t1[1] - group_t0[1] : 0.0;
         stats->max_in_flight = max_in_flight;
         if (time_kernels && err == KV_OK) {
             for (size_t i = 0; i < timing_kind.size(); ++i) {

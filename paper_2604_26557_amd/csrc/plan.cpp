@@ -268,6 +268,42 @@ extern "C" int kv_plan_trim(const kv_plan_t *p, int layer_begin, int layer_end, 
     return KV_OK;
 }
 
+extern "C" int kv_adapt_init(kv_adapt_t *a)
+{
+    if (!a) return KV_EINVAL;
+    a->iteration = 0;
+    for (int g = 0; g < 2; ++g) {
+        a->chosen[g] = -1;
+        a->gbps[g][0] = a->gbps[g][1] = 0.0;
+    }
+    return KV_OK;
+}
+
+extern "C" int kv_adapt_order(const kv_adapt_t *a, int group)
+{
+    if (!a || group < 0 || group > 1) return KV_EINVAL;
+    if (a->iteration <= 1) return KV_ORDER_INTRA;  // warm-up, then the measured overlap-intra iteration
+    if (a->iteration == 2) return KV_ORDER_CROSS;  // the measured overlap-cross iteration
+    return a->chosen[group] >= 0 ? a->chosen[group] : KV_ORDER_INTRA;
+}
+
+extern "C" int kv_adapt_update(kv_adapt_t *a, const kv_pipe_stats_t *st)
+{
+    if (!a || !st) return KV_EINVAL;
+    const uint64_t bytes[2] = {st->bytes_pagecache, st->bytes_direct};
+    const int it = a->iteration;  // 0-based index of the iteration that has just run
+    if (it == 1 || it == 2) {
+        const int order = it == 1 ? KV_ORDER_INTRA : KV_ORDER_CROSS;
+        for (int g = 0; g < 2; ++g)
+            a->gbps[g][order] = st->group_seconds[g] > 0 ? (double)bytes[g] / st->group_seconds[g] / 1e9 : 0.0;
+    }
+    if (it == 2)
+        for (int g = 0; g < 2; ++g)
+            a->chosen[g] = a->gbps[g][KV_ORDER_CROSS] > a->gbps[g][KV_ORDER_INTRA] ? KV_ORDER_CROSS : KV_ORDER_INTRA;
+    a->iteration = it + 1;
+    return KV_OK;
+}
+
 extern "C" int kv_last_hip_error(void) { return g_last_hip_error; }
 
 extern "C" const char *kv_strerror(int code)

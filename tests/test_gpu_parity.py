@@ -350,6 +350,59 @@ def test_pipeline_reload_attention_from_extent(case):
                            q_layers=qd, out_layers=outs, attn_from_extent=True, span_chunks=1)
 
 
+@pytest.mark.parametrize("span_chunks,order_pc,order_direct", [(0, kv.KV_ORDER_INTRA, kv.KV_ORDER_INTRA),
+                                                              (2, kv.KV_ORDER_INTRA, kv.KV_ORDER_CROSS),
+                                                              (0, kv.KV_ORDER_CROSS, kv.KV_ORDER_INTRA)])
+def test_pipeline_overlap_orders(case, span_chunks, order_pc, order_direct):
+    """Both overlap strategies (K then V, or K and V alternating) move the same bytes; the per-group
+    clock runs for every path group that has layers."""
+    cfg, r = case.cfg, case.ref
+    FILL = 0x3C
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    kw = dict(depth=cfg.depth, span_chunks=span_chunks, order_pagecache=order_pc, order_direct=order_direct)
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, **kw)
+    want_region, want_arena = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    qd = [W.query(cfg, l, "cuda") for l in range(cfg.n_layers)]
+    outs = [torch.zeros((len(case.lens), cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+            for _ in range(cfg.n_layers)]
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, view, region, arena,
+                            q_layers=qd, out_layers=outs, **kw)
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+    _attn_check(outs[0], case.expected_attention(0, qd[0].cpu()))
+    assert (st.group_seconds[0] > 0) == (r.n1 > 0) and (st.group_seconds[1] > 0) == (r.n1 < r.L)
+    assert st.max_in_flight <= cfg.depth
+
+
+def test_adaptive_strategy_over_decode_iterations(case):
+    """Five decode iterations driven by the selector: orders follow warm-up / intra / cross / chosen, and
+    every iteration reloads the same bytes."""
+    cfg, r = case.cfg, case.ref
+    region = pinned_bytes(r.region_bytes, 0)
+    arena = np.zeros(max(r.pageable_bytes, 1), dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=cfg.depth)
+    a = kv.kv_adapt_init()
+    seen = []
+    for it in range(5):
+        orders = (kv.kv_adapt_order(a, 0), kv.kv_adapt_order(a, 1))
+        seen.append(orders)
+        k_new, v_new = case.blank_like_source()
+        st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, cfg.n_layers, case.make_view(k_new, v_new), region, arena,
+                                depth=cfg.depth, order_pagecache=orders[0], order_direct=orders[1])
+        _check_restored(case, k_new, v_new, [0, cfg.n_layers - 1])
+        kv.kv_adapt_update(a, st)
+    I, C_ = kv.KV_ORDER_INTRA, kv.KV_ORDER_CROSS
+    assert seen[:3] == [(I, I), (I, I), (C_, C_)]
+    assert seen[3] == seen[4] == (a.chosen[0], a.chosen[1])
+    for g in (0, 1):
+        want = C_ if a.gbps[g][C_] > a.gbps[g][I] else I
+        assert a.chosen[g] == want
+
+
 def test_pipeline_layer_subrange_and_other_chunk_size(case):
     """Only the requested layers move; a different (aligned) chunk size gives the same bytes."""
     cfg, r = case.cfg, case.ref

@@ -252,3 +252,13 @@ def test_trim_zeroes_exactly_the_extent():
     buf = np.full(10 * 512, 0xAB, dtype=np.uint8)
     o.trim(buf, 3 * 512, 4, 512)
     assert (buf[:3 * 512] == 0xAB).all() and not buf[3 * 512:7 * 512].any() and (buf[7 * 512:] == 0xAB).all()
+
+
+# ------------------------------------------------------------------ Sec. IV-C strategy selection
+def test_adapt_order_schedule():
+    INTRA, CROSS = 1, 0
+    assert [o.adapt_order(i, 0.0, 0.0) for i in (1, 2, 3)] == [INTRA, INTRA, CROSS]   # warm-up, intra, cross
+    assert o.adapt_order(4, 11.93, 13.13) == CROSS          # the paper's Group 1 example: cross is faster
+    assert o.adapt_order(4, 13.13, 11.93) == INTRA
+    assert o.adapt_order(9, 5.0, 5.0) == INTRA              # tie keeps the first strategy
+    assert o.adapt_order(1000, 1.0, 2.0) == CROSS           # fixed for all later iterations

@@ -197,3 +197,23 @@ def test_trim_matches_oracle_and_touches_only_extents():
     with pytest.raises(kv.KVError) as e:
         kv.kv_plan_trim(p, 0, 4, region[:ref.region_bytes - 1], arena)
     assert e.value.code == kv.KV_ENOSPC
+
+
+def test_adaptive_selection_matches_oracle():
+    rng = np.random.default_rng(11)
+    for trial in range(50):
+        a = kv.kv_adapt_init()
+        thr = {0: [0.0, 0.0], 1: [0.0, 0.0]}                   # [group][order] as measured
+        for it in range(1, 8):                                  # 1-based decode iterations
+            orders = [kv.kv_adapt_order(a, g) for g in (0, 1)]
+            for g in (0, 1):
+                assert orders[g] == o.adapt_order(it, thr[g][kv.KV_ORDER_INTRA], thr[g][kv.KV_ORDER_CROSS]), (trial, it, g)
+            st = kv.kv_pipe_stats_t()
+            st.bytes_pagecache, st.bytes_direct = 2 * 10**9, 3 * 10**9
+            secs = [float(rng.uniform(0.03, 0.06)), float(rng.uniform(0.04, 0.08))] if trial else [0.05, 0.05]
+            st.group_seconds[0], st.group_seconds[1] = secs
+            if it in (2, 3):                                    # only these two iterations are measured
+                thr[0][orders[0]] = 2.0 / secs[0]
+                thr[1][orders[1]] = 3.0 / secs[1]
+            kv.kv_adapt_update(a, st)
+        assert a.iteration == 7
