@@ -310,6 +310,17 @@ def main():
                                    "reload_frac_of_link": round(nb / b.wall_s / 1e9 / link["h2d"], 3)}
         res["per_path"] = per_path
 
+        # the two overlap strategies of the adaptive pipeline, one reload each, per path group
+        orders = {}
+        for name, code in (("intra", kv.KV_ORDER_INTRA), ("cross", kv.KV_ORDER_CROSS)):
+            st = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD, 0, L, dst_view, region, arena, depth=cfg.depth,
+                                    span_chunks=args.span_chunks, host_workers=args.host_workers,
+                                    order_pagecache=code, order_direct=code)
+            orders[name] = {g: round(b / s_ / 1e9, 2) if s_ > 0 else None
+                            for g, b, s_ in (("pagecache_GBps", st.bytes_pagecache, st.group_seconds[0]),
+                                             ("direct_GBps", st.bytes_direct, st.group_seconds[1]))}
+        res["reload_overlap_orders"] = orders
+
         # overlap fraction = (T_serial - T_pipe) / (T_serial - T_link): T_serial is one step with every
         # stage run to completion before the next starts, T_link the same bytes at the measured link rate
         sa = kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, src_view, region, arena, depth=1, serialize=True,
