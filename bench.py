@@ -22,6 +22,23 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --leg kernels` on the
+# llama8b_32k workload (profiles/pmc_traffic_llama8b_32k.md), each counter scaled by what it reads for a
+# plain 128 MiB device-to-device copy in the same run.  Valid only for the kernel sources they were taken
+# with: the hash below covers the two kernel files, and a mismatch reports traffic as null.
+PMC_TRAFFIC = {"sha": "ed4bf653ffb85392", "workload": "llama8b_32k",
+               "kv_layout_kernel<pack>": 268460082, "kv_layout_kernel<unpack>": 268461295,
+               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135516905 + 1147703}
+
+
+def kernel_sources_hash() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for fn in ("layout_kernels.hip", "attn_kernels.hip"):
+        with open(os.path.join(ROOT, "paper_2604_26557_amd", "csrc", fn), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -343,6 +360,9 @@ def main():
         rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], tpl * (tensor_payload + tensor_image), where),
               roof("kv_layout_kernel<unpack>", kl["unpack_us"], tpl * 2 * tensor_payload, where),
               roof("kv_attn_partial_kernel+kv_attn_combine_kernel", kl["attn_us"], 2 * tensor_payload, where)]
+        if cfg.name == PMC_TRAFFIC["workload"] and kernel_sources_hash() == PMC_TRAFFIC["sha"]:
+            for r in rl:
+                r["traffic"] = PMC_TRAFFIC.get(r["kernel"])
         res["rooflines"] = rl
         res["decode_attn_us_per_layer"] = round(kl["attn_us"], 2)
         # the dominant kernel of a step: the one with the most GPU time over its launches
