@@ -21,6 +21,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kMaxSegs = 32;
+constexpr int kTblStage = 64;  // block-table entries one workgroup can stage in LDS
 
 // Attention-side addressing, in 16-byte vectors.
 struct SrcDesc {
@@ -81,6 +82,22 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
     const int ty = tid >> rx_log2;
     const int hd = s.H * s.dvec;
 
+    // Paged source, one sequence per segment: the few block-table entries this tile touches are staged in
+    // LDS once, so the per-token lookup is not a second dependent trip to memory.
+    __shared__ int sh_tbl[kTblStage];
+    int j_first = 0;
+    bool tbl_in_lds = false;
+    if (PAGED && sg.b >= 0) {
+        j_first = (sg.tok0 + t_begin) / s.bt;
+        const int nj = (sg.tok0 + t_end - 1) / s.bt - j_first + 1;
+        if (nj <= kTblStage) {  // uniform over the workgroup
+            const int *row = s.table + (long long)sg.b * s.max_blocks;
+            for (int i = tid; i < nj; i += kThreads) sh_tbl[i] = row[j_first + i];
+            __syncthreads();
+            tbl_in_lds = true;
+        }
+    }
+
     for (int r = rx; r < rowv; r += RX) {
         int b, rem;
         if (sg.b >= 0) { b = sg.b; rem = r; } else { b = r / hd; rem = r - b * hd; }
@@ -103,7 +120,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
                     if (PAGED) {
                         const int j = s.bt_shift >= 0 ? (tok >> s.bt_shift) : (tok / s.bt);
                         const int slot = tok - j * s.bt;
-                        const int blk = tbl[j];
+                        const int blk = tbl_in_lds ? sh_tbl[j - j_first] : tbl[j];
                         ok[u] = (unsigned)blk < (unsigned)s.n_pool;  // ids outside the pool are skipped
                         a[u] = (((long long)blk * s.H + h) * s.bt + slot) * s.dvec + dv;
                     } else {
