@@ -493,3 +493,63 @@ def test_decode_append(cfg):
     with pytest.raises(kv.KVError) as e:
         kv.kv_append_tokens(case.plan, 0, cfg.n_layers, case.make_view(case.k, case.v, [n + 1 for n in lens]), region, arena)
     assert e.value.code == kv.KV_ERANGE
+
+
+# ------------------------------------------------------------------------------------------ random shapes
+def _random_configs(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        D = int(rng.choice([64, 128, 256]))
+        H = int(rng.integers(1, 7))
+        G = int(rng.choice([1, 2, 3, 4, 8]))
+        B = int(rng.integers(1, 5))
+        sector = int(rng.choice([512, 4096]))
+        per_seq = bool(rng.integers(0, 2))
+        paged = bool(rng.integers(0, 2))
+        row = (H if per_seq else B * H) * D * 2
+        unit = sector // np.gcd(sector, row)                   # fewest rows that end on a sector boundary
+        chunk = int(unit * rng.integers(1, 6))
+        dtype = W.F16 if rng.integers(0, 2) else W.BF16
+        if per_seq:
+            lo = int(rng.integers(1, 40))
+            cfg = W.KVConfig(f"rand{i}", 100 + i, 2, H, H * G, D, B, dtype, sector, chunk, int(rng.integers(1, 5)),
+                             W.PER_SEQ, W.PAGED if paged else W.BHSD, 0, len_range=(lo, lo + int(rng.integers(0, 300))))
+        else:
+            cfg = W.KVConfig(f"rand{i}", 100 + i, 2, H, H * G, D, B, dtype, sector, chunk, int(rng.integers(1, 5)),
+                             W.TOKEN_MAJOR, W.PAGED if paged else W.BHSD, int(rng.integers(1, 400)))
+        # one of the two layers on the page-cache path in half of the cases
+        if rng.integers(0, 2):
+            lens = W.seq_lens(cfg)
+            nb = o.tensor_blocks(per_seq, lens, H, D, 2, sector)[0]
+            cfg = W.shrink(cfg, pc_budget_bytes=2 * nb * sector)
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_configs(24, 2024), ids=lambda c: c.name)
+def test_random_shapes_end_to_end(cfg):
+    """Seeded random shapes (head counts, group sizes, head dims, batch, sector, chunk, both extent modes,
+    both layouts, mixed paths): offload bytes, round trip and attention against the checker."""
+    case = Case(cfg, "cuda", gen_device="cpu", raw=False)
+    r = case.ref
+    FILL = 0x42
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=cfg.depth,
+                       span_chunks=cfg.index % 3)
+    want_region, want_arena = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    k_new, v_new = case.blank_like_source()
+    view = case.make_view(k_new, v_new)
+    qs = [W.query(cfg, l, "cpu") for l in range(cfg.n_layers)]
+    qd = [q.cuda() for q in qs]
+    outs = [torch.full((len(case.lens), cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+            for _ in range(cfg.n_layers)]
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, view, region, arena, depth=cfg.depth,
+                       q_layers=qd, out_layers=outs, span_chunks=(cfg.index + 1) % 3,
+                       order_pagecache=cfg.index % 2, order_direct=(cfg.index // 2) % 2)
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+    for l in range(cfg.n_layers):
+        _attn_check(outs[l], case.expected_attention(l, qs[l]))
