@@ -456,7 +456,11 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         ws_bytes = kv_decode_attn_workspace(p, attn->n_splits, max_len);
     }
     const size_t n_timing = time_kernels ? 2 * (spans.size() + 2 * (size_t)(layer_end - layer_begin)) : 0;
-    int rc = ensure_pipeline(p, n_slots, slot_bytes, depth, chunk_bytes, any_pc, n_workers, ws_bytes, n_timing);
+    // Ring entries (completion event, host-copy counter, bounce slot).  `depth` bounds the transfers in
+    // flight; with page-cache-path layers the ring is twice as long, so that a bounce slot can wait for its
+    // host copy (the memcpy hop is not a device command) without holding back the next transfer.
+    const size_t NB = any_pc ? 2 * (size_t)depth : (size_t)depth;
+    int rc = ensure_pipeline(p, n_slots, slot_bytes, (int)NB, chunk_bytes, any_pc, n_workers, ws_bytes, n_timing);
     if (rc != KV_OK) return rc;
     kv_pipeline *q = p->pipe;
     char *staging = (char *)q->staging;
@@ -489,29 +493,32 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         const int g = spans[chunks[c].span].path == KV_PATH_PAGECACHE ? 0 : 1;
         if (group_t0[g] < 0) group_t0[g] = now_s();
     };
-    // Chunk c owns ring entry c % depth from its start until it is known complete.
-    auto wait_complete = [&](size_t c) -> int {
-        Entry &e = q->ring[c % (size_t)depth];
-        KV_HIP(hipEventSynchronize(e.ev));
-        spin_until_zero(e.pending);
-        for (int g = 0; g < 2; ++g)
-            if ((long long)c == group_last[g]) group_t1[g] = now_s();
-        return KV_OK;
-    };
-    auto acquire = [&](size_t c) -> int {  // make ring entry of chunk c free
-        while (c >= n_waited + (size_t)depth) {
-            int r = wait_complete(n_waited);
-            if (r != KV_OK) return r;
+    // Chunk c owns ring entry c % NB.  Transfers are harvested in issue order; n_waited counts them.
+    auto harvest_until = [&](size_t upto) -> int {  // transfers of chunks [0, upto) are complete
+        while (n_waited < upto) {
+            KV_HIP(hipEventSynchronize(q->ring[n_waited % NB].ev));
+            for (int g = 0; g < 2; ++g)
+                if ((long long)n_waited == group_last[g]) group_t1[g] = now_s();
             ++n_waited;
         }
+        return KV_OK;
+    };
+    // At most `depth` transfers outstanding: the oldest is harvested before chunk c is issued.
+    auto transfer_slot = [&](size_t c) -> int { return c >= (size_t)depth ? harvest_until(c + 1 - (size_t)depth) : KV_OK; };
+    // Ring entry (and bounce slot) of chunk c is free once chunk c - NB has left it, host copy included.
+    auto entry_free = [&](size_t c) -> int {
+        if (c < NB) return KV_OK;
+        int r = harvest_until(c - NB + 1);
+        if (r != KV_OK) return r;
+        spin_until_zero(q->ring[c % NB].pending);
         return KV_OK;
     };
     auto host_ptr = [&](const Chunk &ch) -> char * {
         return (spans[ch.span].path == KV_PATH_DIRECT ? (char *)lba_region : (char *)pageable) + ch.host_off;
     };
-    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % (size_t)depth) * chunk_bytes; };
+    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % NB) * chunk_bytes; };
     auto fan_out = [&](size_t c, void *dst, const void *src, size_t bytes, hipEvent_t ev) {
-        Entry &e = q->ring[c % (size_t)depth];
+        Entry &e = q->ring[c % NB];
         int pieces = (int)std::min<size_t>((size_t)pieces_max, std::max<size_t>(1, bytes / (256 * 1024)));
         e.pending.store(pieces, std::memory_order_release);
         const size_t step = kvb::round_up(kvb::ceil_div(bytes, (uint64_t)pieces), 4096);
@@ -565,9 +572,9 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 if (serialize) KV_HIP_BRK(hipStreamSynchronize(q->s_compute));
                 used = 0;
             }
-            if ((err = acquire(c)) != KV_OK) break;
+            if ((err = entry_free(c)) != KV_OK || (err = transfer_slot(c)) != KV_OK) break;
             note_issue(c);
-            Entry &e = q->ring[c % (size_t)depth];
+            Entry &e = q->ring[c % NB];
             const int s = (int)(c % (size_t)ns);
             hipStream_t st = q->s_copy[s];
             if (!(used >> s & 1)) {  // first chunk of this span on this stream: order it after the pack
@@ -584,8 +591,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             }
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(c + 1 - n_waited));
             if (serialize) {  // every stage to completion before the next starts
-                while (n_waited <= c && err == KV_OK) { err = wait_complete(n_waited); ++n_waited; }
-                if (err != KV_OK) break;
+                if ((err = harvest_until(c + 1)) != KV_OK) break;
+                spin_until_zero(e.pending);
             }
             if (ch.last) {
                 for (int k = 0; k < ns && err == KV_OK; ++k)
@@ -598,28 +605,28 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             }
         }
     } else {
-        // Reload.  Page-cache-path chunks are started (arena -> bounce memcpy) a few commands ahead of
-        // their H2D issue; a direct chunk starts when it is issued.
-        const size_t look = serialize ? 1 : std::max<size_t>(1, (size_t)depth / 2);
+        // Reload.  Page-cache-path chunks are started (arena -> bounce memcpy) up to `depth` commands ahead
+        // of their H2D issue; a direct chunk starts when it is issued.
+        const size_t look = serialize ? 1 : (size_t)depth;
         size_t cs = 0;  // next chunk to start
         for (size_t ci = 0; ci < N && err == KV_OK; ++ci) {
             while (cs < N && err == KV_OK) {
                 const bool pc = spans[chunks[cs].span].path == KV_PATH_PAGECACHE;
                 if (cs >= ci + (pc ? look : 1)) break;
-                if ((err = acquire(cs)) != KV_OK) break;
+                if ((err = entry_free(cs)) != KV_OK) break;
                 note_issue(cs);
-                Entry &e = q->ring[cs % (size_t)depth];
+                Entry &e = q->ring[cs % NB];
                 if (pc) fan_out(cs, bounce_ptr(cs), host_ptr(chunks[cs]), chunks[cs].bytes, nullptr);
                 else e.pending.store(0, std::memory_order_release);
                 ++cs;
-                max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(cs - n_waited));
             }
             if (err != KV_OK) break;
+            if ((err = transfer_slot(ci)) != KV_OK) break;
             const Chunk &ch = chunks[ci];
             const Span &sp = spans[ch.span];
             const size_t slot = (size_t)ch.span % n_slots;
             char *img = staging + slot * slot_bytes;
-            Entry &e = q->ring[ci % (size_t)depth];
+            Entry &e = q->ring[ci % NB];
             const int s = (int)(ci % (size_t)ns);
             hipStream_t st = q->s_copy[s];
             if (ch.first) used = 0;
@@ -634,7 +641,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st));
             }
             KV_HIP_BRK(hipEventRecord(e.ev, st));
-            if (serialize) KV_HIP_BRK(hipEventSynchronize(e.ev));
+            max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(ci + 1 - n_waited));
+            if (serialize && (err = harvest_until(ci + 1)) != KV_OK) break;
             if (stats) {
                 stats->n_chunks++;
                 (sp.path == KV_PATH_DIRECT ? stats->bytes_direct : stats->bytes_pagecache) += ch.bytes;
