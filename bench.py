@@ -173,7 +173,7 @@ def main():
                     help="reload: decode attention reads the staged extent images, nothing is unpacked")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -14,7 +14,7 @@
  * force sector sets on tiny shapes, NumPy transposes for the byte order, closed forms
  * for attention.  No function here is "parity unpinned".
  *
- * Readings taken where the paper leaves a choice (each restated in the design doc):
+ * Readings taken where the paper leaves a choice:
  *  - n_blocks uses ceiling division and the pad bytes are zero; under the paper's
  *    alignment precondition (Sec. IV-B) this equals Eq. 5.
  *  - only direct-path tensors consume LBAs; page-cache-path tensors get byte offsets
