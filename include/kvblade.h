@@ -134,6 +134,10 @@ typedef struct kv_view {
     /* valid tokens per sequence */
     const int32_t *seq_lens_host; /* host [B] */
     const int32_t *seq_lens_dev;  /* device [B] (decode attention reads it) */
+    /* KV_LAYOUT_BHSD, decode attention only, optional: element offset (a multiple of 8) of sequence b's
+     * first row, used instead of b*stride_b (sequences that are not equally spaced).  Both or neither. */
+    const int64_t *seq_off_host; /* host [B] or NULL */
+    const int64_t *seq_off_dev;  /* device [B] or NULL */
 } kv_view_t;
 
 typedef struct kv_attn_args {
@@ -156,7 +160,7 @@ typedef struct kv_attn_args {
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 
-#define KV_PIPE_ATTN_FROM_EXTENT 4u /* KV_DIR_RELOAD_ATTN, token-major plans, whole-extent spans only: decode
+#define KV_PIPE_ATTN_FROM_EXTENT 4u /* KV_DIR_RELOAD_ATTN, whole-extent spans only: decode
                                        attention reads the staged extent images directly (extent order is a
                                        strided [B,H,S,D] view) and nothing is unpacked: the view's K/V buffers
                                        are neither read nor written */

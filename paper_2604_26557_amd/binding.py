@@ -74,7 +74,8 @@ class kv_view_t(C.Structure):
                 ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_s", C.c_int64),
                 ("s_alloc", C.c_int32), ("block_tokens", C.c_int32), ("n_pool_blocks", C.c_int32),
                 ("max_blocks_per_seq", C.c_int32), ("block_table", C.c_void_p),
-                ("seq_lens_host", C.POINTER(C.c_int32)), ("seq_lens_dev", C.c_void_p)]
+                ("seq_lens_host", C.POINTER(C.c_int32)), ("seq_lens_dev", C.c_void_p),
+                ("seq_off_host", C.POINTER(C.c_int64)), ("seq_off_dev", C.c_void_p)]
 
 
 class kv_attn_args_t(C.Structure):

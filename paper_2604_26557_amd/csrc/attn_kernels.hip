@@ -43,6 +43,7 @@ struct AttnParams {
     float *part_acc;       // [B, Hq, n_splits, D]
     float *part_ml;        // [B, Hq, n_splits, 2]
     long long sb, sh, ss;  // strided layout, in 16-byte vectors
+    const long long *seq_off;  // strided layout, optional: element offset of each sequence (replaces b*sb)
     const int *table;      // paged layout
     int max_blocks, bt, bt_shift, n_pool;
     int H, Hq, G;
@@ -142,7 +143,7 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
 #pragma unroll
         for (int e = 0; e < AE; ++e) acc[g][e] = 0.f;
 
-    const long long head_off = PAGED ? 0 : (long long)b * p.sb + (long long)h * p.sh;
+    const long long head_off = PAGED ? 0 : (p.seq_off ? p.seq_off[b] / 8 : (long long)b * p.sb) + (long long)h * p.sh;
     const int *tbl = PAGED ? p.table + (long long)b * p.max_blocks : nullptr;
     // vector index of the first element of token row `row`; ok = false for a block id outside the pool
     auto row_base = [&](int row, bool &ok) -> long long {
@@ -461,12 +462,17 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
         if (kv->stride_b < 0 || kv->stride_h < 0 || kv->stride_s < p->D) return KV_EINVAL;
         if ((kv->stride_b | kv->stride_h | kv->stride_s) & 7) return KV_EINVAL;
         if (max_len > kv->s_alloc) return KV_ERANGE;
-        if (max_len > 0) {
-            const uint64_t max_elem = (uint64_t)(p->B - 1) * kv->stride_b + (uint64_t)(p->H - 1) * kv->stride_h +
-                                      (uint64_t)(max_len - 1) * kv->stride_s + p->D;
+        if ((kv->seq_off_host == nullptr) != (kv->seq_off_dev == nullptr)) return KV_EINVAL;
+        for (int b = 0; b < p->B; ++b) {  // the last element any sequence reads must lie inside the buffer
+            const int len = kv->seq_lens_host[b];
+            if (len == 0) continue;
+            if (kv->seq_off_host && (kv->seq_off_host[b] < 0 || (kv->seq_off_host[b] & 7))) return KV_EINVAL;
+            const uint64_t base = kv->seq_off_host ? (uint64_t)kv->seq_off_host[b] : (uint64_t)b * kv->stride_b;
+            const uint64_t max_elem = base + (uint64_t)(p->H - 1) * kv->stride_h + (uint64_t)(len - 1) * kv->stride_s + p->D;
             if (max_elem * 2 > kv->layer_bytes) return KV_ERANGE;
         }
         a.sb = kv->stride_b / 8; a.sh = kv->stride_h / 8; a.ss = kv->stride_s / 8;
+        a.seq_off = (const long long *)kv->seq_off_dev;
     } else if (paged) {
         if (!kv->block_table || kv->block_tokens < 1 || kv->n_pool_blocks < 0) return KV_EINVAL;
         if ((uint64_t)kv->n_pool_blocks * p->H * kv->block_tokens * p->D * 2 > kv->layer_bytes) return KV_ERANGE;

@@ -155,6 +155,7 @@ int check_view(const kv_plan *p, const kv_view_t *v, int layer)
     if (layer < 0 || layer >= p->L || layer >= v->n_layers) return KV_ERANGE;
     if (!v->k_layers[layer] || !v->v_layers[layer]) return KV_EINVAL;
     if (((uintptr_t)v->k_layers[layer] | (uintptr_t)v->v_layers[layer]) & 15) return KV_EINVAL;
+    if (v->seq_off_host || v->seq_off_dev) return KV_EINVAL;  // per-sequence offsets are for attention only
     if (v->layout == KV_LAYOUT_BHSD) {
         if (v->stride_b < 0 || v->stride_h < 0 || v->stride_s < 0 || v->s_alloc < 0) return KV_EINVAL;
         if ((v->stride_b | v->stride_h | v->stride_s) & 7) return KV_EINVAL;

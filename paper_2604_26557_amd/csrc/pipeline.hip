@@ -17,6 +17,7 @@
 // (the runtime's per-command cost dominates D2H copies of a few hundred KiB).  Both are options.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 #include <condition_variable>
@@ -185,6 +186,8 @@ struct kv_pipeline {
     Workers workers;
     // decode append: pinned landing buffer for the packed rows, and per (tensor, sequence) the image of
     // the last partly filled sector (so that only the first append after an offload has to read it back)
+    void *seq_off_dev = nullptr;  // per-sequence element offsets inside an extent image (attention from extents)
+    std::vector<int64_t> seq_off_host;
     void *append_host = nullptr;
     size_t append_host_bytes = 0;
     std::vector<char> tail_img;
@@ -204,6 +207,7 @@ struct kv_pipeline {
         if (staging) (void)hipFree(staging);
         if (bounce) (void)hipHostFree(bounce);
         if (append_host) (void)hipHostFree(append_host);
+        if (seq_off_dev) (void)hipFree(seq_off_dev);
         if (attn_ws) (void)hipFree(attn_ws);
         for (auto st : s_copy) if (st) (void)hipStreamDestroy(st);
         if (s_compute) (void)hipStreamDestroy(s_compute);
@@ -305,7 +309,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const bool time_kernels = opts && (opts->flags & KV_PIPE_TIME_KERNELS);
     const bool serialize = opts && (opts->flags & KV_PIPE_SERIALIZE);
     const bool attn_from_extent = opts && (opts->flags & KV_PIPE_ATTN_FROM_EXTENT);
-    if (attn_from_extent && (dir != KV_DIR_RELOAD_ATTN || p->mode != KV_TOKEN_MAJOR || span_chunks != 0)) return KV_EINVAL;
+    if (attn_from_extent && (dir != KV_DIR_RELOAD_ATTN || span_chunks != 0)) return KV_EINVAL;
     if (span_chunks < 0 || n_workers > 64) return KV_EINVAL;
     const bool offload_dir = dir == KV_DIR_OFFLOAD;
     int ns = opts ? opts->copy_streams : 0;
@@ -463,6 +467,12 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     int rc = ensure_pipeline(p, n_slots, slot_bytes, (int)NB, chunk_bytes, any_pc, n_workers, ws_bytes, n_timing);
     if (rc != KV_OK) return rc;
     kv_pipeline *q = p->pipe;
+    if (attn_from_extent && p->mode == KV_PER_SEQ && !q->seq_off_dev) {
+        q->seq_off_host.resize((size_t)p->B);
+        for (int b = 0; b < p->B; ++b) q->seq_off_host[b] = (int64_t)(p->seq_base[b] * sec / 2);
+        KV_HIP(hipMalloc(&q->seq_off_dev, sizeof(int64_t) * (size_t)p->B));
+        KV_HIP(hipMemcpy(q->seq_off_dev, q->seq_off_host.data(), sizeof(int64_t) * (size_t)p->B, hipMemcpyHostToDevice));
+    }
     char *staging = (char *)q->staging;
     const int pieces_max = std::max(1, q->workers.size());
 
@@ -685,10 +695,18 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                         ev.k_layers = ext_k.data();
                         ev.v_layers = ext_v.data();
                         ev.layer_bytes = image;
-                        ev.stride_b = (int64_t)p->H * p->D;
                         ev.stride_h = p->D;
-                        ev.stride_s = (int64_t)p->B * p->H * p->D;
-                        ev.s_alloc = p->cap[0];
+                        if (p->mode == KV_TOKEN_MAJOR) {
+                            ev.stride_b = (int64_t)p->H * p->D;
+                            ev.stride_s = (int64_t)p->B * p->H * p->D;
+                            ev.s_alloc = p->cap[0];
+                        } else {  // per-sequence sub-extents (cap_b, H, D), each at its own sector offset
+                            ev.stride_b = 0;
+                            ev.stride_s = (int64_t)p->H * p->D;
+                            ev.s_alloc = *std::max_element(p->cap.begin(), p->cap.end());
+                            ev.seq_off_host = q->seq_off_host.data();
+                            ev.seq_off_dev = (const int64_t *)q->seq_off_dev;
+                        }
                         time_begin(KV_KERNEL_ATTN_PARTIAL);
                         err = kv_decode_attn(p, &ev, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
                                              attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);

@@ -327,8 +327,6 @@ def test_pipeline_reload_attention_from_extent(case):
     """Decode attention fed straight from the staged extent images (no unpack): same outputs, and the
     destination view is neither read nor written."""
     cfg, r = case.cfg, case.ref
-    if r.per_seq:
-        pytest.skip("token-major extents only")
     region = pinned_bytes(r.region_bytes, 0)
     arena = np.zeros(max(r.pageable_bytes, 1), dtype=np.uint8)
     kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=cfg.depth)
