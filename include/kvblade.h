@@ -156,7 +156,8 @@ typedef struct kv_attn_args {
 #define KV_PIPE_SERIALIZE 2u    /* run every stage (kernel, chunk transfer, host copy) to completion before
                                    the next starts: the no-overlap reference for the overlap fraction */
 
-#define KV_COPY_AUTO 0   /* D2H: copy kernel; H2D: hipMemcpyAsync (the faster of the two, as measured) */
+#define KV_COPY_AUTO 0   /* the faster of the two as measured: H2D hipMemcpyAsync; D2H hipMemcpyAsync for commands
+                            of >= 2 MiB at depth >= 4, else the copy kernel */
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 
@@ -173,7 +174,8 @@ typedef struct kv_pipe_opts {
                              (K and V in one launch) */
     int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
     uint32_t flags;       /* KV_PIPE_* */
-    int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (2 D2H, 4 H2D);
+    int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (2 for the copy kernel,
+                             4 for hipMemcpyAsync);
                              never more than depth */
     int32_t d2h_mode;     /* KV_COPY_* for offload transfers */
     int32_t h2d_mode;     /* KV_COPY_* for reload transfers */

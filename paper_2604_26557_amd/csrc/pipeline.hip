@@ -13,8 +13,9 @@
 // start-up and tail of one transfer hide behind the next); events order pack -> D2H and
 // H2D -> unpack -> attention and guard staging-slot reuse.  All streams keep the default priority.
 // Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D is fastest as
-// hipMemcpyAsync over four streams; D2H is fastest as this file's own copy kernel over two streams
-// (the runtime's per-command cost dominates D2H copies of a few hundred KiB).  Both are options.
+// hipMemcpyAsync over four streams; D2H of small commands is fastest as this file's own copy kernel
+// over two streams (the runtime's per-command cost dominates D2H copies of a few hundred KiB), D2H of
+// 2 MiB commands and more as hipMemcpyAsync over four streams.  Both engines are options.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -317,14 +318,19 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const int d2h_mode = opts ? opts->d2h_mode : KV_COPY_AUTO, h2d_mode = opts ? opts->h2d_mode : KV_COPY_AUTO;
     if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
         return KV_EINVAL;
-    const bool d2h_kernel = d2h_mode != KV_COPY_MEMCPY;  // auto: copy kernel
-    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;  // auto: hipMemcpyAsync
+    // Engine defaults by measurement: H2D is fastest as hipMemcpyAsync over four streams at every chunk
+    // size; D2H is fastest as hipMemcpyAsync over four streams for commands of 2 MiB and more when four
+    // may be in flight, and as the copy kernel over two streams for smaller or fewer commands.
+    const uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
+    const bool d2h_big = cmd_bytes >= (2ull << 20) && depth >= 4;
+    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && !d2h_big);
+    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;
     const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
     const int order_direct = opts ? opts->order_direct : KV_ORDER_CROSS;
     if ((order_pc != KV_ORDER_CROSS && order_pc != KV_ORDER_INTRA) ||
         (order_direct != KV_ORDER_CROSS && order_direct != KV_ORDER_INTRA))
         return KV_EINVAL;
-    if (ns == 0) ns = offload_dir ? 2 : 4;
+    if (ns == 0) ns = offload_dir && d2h_kernel ? 2 : 4;
     ns = std::min(ns, depth);
     if (stats) std::memset(stats, 0, sizeof(*stats));
     if (layer_begin == layer_end) return KV_OK;
