@@ -157,7 +157,7 @@ typedef struct kv_attn_args {
                                    the next starts: the no-overlap reference for the overlap fraction */
 
 #define KV_COPY_AUTO 0   /* the faster of the two as measured: H2D hipMemcpyAsync; D2H hipMemcpyAsync for commands
-                            of >= 2 MiB at depth >= 4, else the copy kernel */
+                            of >= 8 MiB, or >= 2 MiB at depth >= 4, else the copy kernel */
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 

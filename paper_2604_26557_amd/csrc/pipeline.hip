@@ -15,7 +15,7 @@
 // Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D is fastest as
 // hipMemcpyAsync over four streams; D2H of small commands is fastest as this file's own copy kernel
 // over two streams (the runtime's per-command cost dominates D2H copies of a few hundred KiB), D2H of
-// 2 MiB commands and more as hipMemcpyAsync over four streams.  Both engines are options.
+// large commands as hipMemcpyAsync over up to four streams.  Both engines are options.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -319,10 +319,10 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
         return KV_EINVAL;
     // Engine defaults by measurement: H2D is fastest as hipMemcpyAsync over four streams at every chunk
-    // size; D2H is fastest as hipMemcpyAsync over four streams for commands of 2 MiB and more when four
-    // may be in flight, and as the copy kernel over two streams for smaller or fewer commands.
+    // size; D2H is fastest as hipMemcpyAsync over up to four streams for commands of 8 MiB and more, and
+    // of 2 MiB and more when four may be in flight; as the copy kernel over two streams otherwise.
     const uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
-    const bool d2h_big = cmd_bytes >= (2ull << 20) && depth >= 4;
+    const bool d2h_big = cmd_bytes >= (8ull << 20) || (cmd_bytes >= (2ull << 20) && depth >= 4);
     const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && !d2h_big);
     const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;
     const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
