@@ -26,9 +26,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # llama8b_32k workload (profiles/pmc_traffic_llama8b_32k.md), each counter scaled by what it reads for a
 # plain 128 MiB device-to-device copy in the same run.  Valid only for the kernel sources they were taken
 # with: the hash below covers the two kernel files, and a mismatch reports traffic as null.
-PMC_TRAFFIC = {"sha": "ed4bf653ffb85392", "workload": "llama8b_32k",
-               "kv_layout_kernel<pack>": 268460082, "kv_layout_kernel<unpack>": 268461295,
-               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135516905 + 1147703}
+PMC_TRAFFIC = {"sha": "6989982857319810", "workload": "llama8b_32k",
+               "kv_layout_kernel<pack>": 268459785, "kv_layout_kernel<unpack>": 268459928,
+               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135512931 + 1147704}
 
 
 def kernel_sources_hash() -> str:
