@@ -181,6 +181,9 @@ typedef struct kv_pipe_opts {
     int32_t h2d_mode;     /* KV_COPY_* for reload transfers */
     int32_t order_pagecache; /* KV_ORDER_* for page-cache-path layers (the two overlap strategies of Sec. IV-C) */
     int32_t order_direct;    /* KV_ORDER_* for direct-path layers */
+    uint64_t max_cmd_bytes;  /* transfer-size limit of one command (MDTS of Eq. 7), 0 = none: a chunk larger than
+                                align_down(max_cmd_bytes, sector) moves as several commands of at most that
+                                size (Eq. 8-11 on the chunk), each counted against depth */
 } kv_pipe_opts_t;
 
 typedef struct kv_pipe_stats {
@@ -241,6 +244,17 @@ int kv_plan_translate(const kv_plan_t *plan, int layer, int kind, int seq, int t
  */
 int kv_plan_chunk_cmds(const kv_plan_t *plan, int layer, int kind, int seq, int chunk_tokens,
                        kv_cmd_t *out, int cap, int *n);
+
+/*
+ * kv_plan_range_cmds -- Alg. 2 for token rows [tok0, tok0+ntok) of (layer, kind, seq) (same rules and
+ * errors as kv_plan_translate), then Eq. 7-11 on that request with the chunk size taken from a device
+ * transfer-size limit: chunk_size = align_down(mdts_bytes, sector) (Eq. 7; mdts_bytes = 0 takes the
+ * plan's chunk_tokens*row_bytes; KV_EINVAL if the limit is below one sector).  buf_off counts from the
+ * request's first byte; a command need not hold whole token rows: tok0/ntok name the rows its payload
+ * bytes touch.  Output convention as kv_plan_chunk_cmds.
+ */
+int kv_plan_range_cmds(const kv_plan_t *plan, int layer, int kind, int seq, int tok0, int ntok,
+                       uint64_t mdts_bytes, kv_cmd_t *out, int cap, int *n);
 
 /* ------------------------------------------------------------------------------------------ */
 /* Kernels (asynchronous on the given stream)                                                 */

@@ -177,6 +177,12 @@ int orc_translate(uint64_t lba_start, const int64_t f[3], const int64_t d[3], co
     return ORC_OK;
 }
 
+/* Eq. 7: the largest LBA-aligned size within the device's maximum data transfer size. */
+uint64_t orc_chunk_size(uint64_t mdts_bytes, uint64_t lba_size)
+{
+    return mdts_bytes / lba_size * lba_size;
+}
+
 /*
  * Eq. 7-11: chunking of one request.  chunk_bytes is a multiple of lba_size (Eq. 7 makes it
  * so from MDTS); n_chunks = ceil(req_bytes / chunk_bytes); n_maxBlocks = chunk_bytes / lba_size;

@@ -55,6 +55,8 @@ def lib():
         _lib.orc_translate.restype = C.c_int
         _lib.orc_translate.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
                                        C.c_void_p, C.c_void_p]
+        _lib.orc_chunk_size.restype = C.c_uint64
+        _lib.orc_chunk_size.argtypes = [C.c_uint64, C.c_uint64]
         _lib.orc_chunk_cmds.restype = C.c_int64
         _lib.orc_chunk_cmds.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_int64,
                                         C.c_void_p, C.c_void_p, C.c_void_p]
@@ -137,6 +139,11 @@ def translate(lba_start: int, shape_src, shape_tgt, idx, e: int, lba_size: int):
     s, r = C.c_uint64(), C.c_uint64()
     rc = lib().orc_translate(lba_start, _p(f), _p(d), _p(i), e, lba_size, C.byref(s), C.byref(r))
     return rc, int(s.value), int(r.value)
+
+
+def chunk_size(mdts_bytes: int, lba_size: int) -> int:
+    """Eq. 7: align_down(MDTS, lba_size)."""
+    return int(lib().orc_chunk_size(mdts_bytes, lba_size))
 
 
 def chunk_cmds(slba_star: int, req_bytes: int, chunk_bytes: int, lba_size: int):

@@ -33,7 +33,7 @@ KV_ORDER_CROSS, KV_ORDER_INTRA = 0, 1
 
 EXPORTS = [
     "kv_layout_plan", "kv_plan_destroy", "kv_plan_info", "kv_plan_tensor", "kv_plan_seq_base",
-    "kv_plan_translate", "kv_plan_chunk_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
+    "kv_plan_translate", "kv_plan_chunk_cmds", "kv_plan_range_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
     "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
 ]
@@ -86,7 +86,7 @@ class kv_attn_args_t(C.Structure):
 class kv_pipe_opts_t(C.Structure):
     _fields_ = [("span_chunks", C.c_int32), ("host_workers", C.c_int32), ("flags", C.c_uint32),
                 ("copy_streams", C.c_int32), ("d2h_mode", C.c_int32), ("h2d_mode", C.c_int32),
-                ("order_pagecache", C.c_int32), ("order_direct", C.c_int32)]
+                ("order_pagecache", C.c_int32), ("order_direct", C.c_int32), ("max_cmd_bytes", C.c_uint64)]
 
 
 class kv_pipe_stats_t(C.Structure):
@@ -127,6 +127,7 @@ def lib() -> C.CDLL:
         L.kv_plan_seq_base.argtypes = [vp, i, C.POINTER(C.c_uint64)]
         L.kv_plan_translate.argtypes = [vp, i, i, i, i, i, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.kv_plan_chunk_cmds.argtypes = [vp, i, i, i, i, C.POINTER(kv_cmd_t), i, C.POINTER(i)]
+        L.kv_plan_range_cmds.argtypes = [vp, i, i, i, i, i, C.c_uint64, C.POINTER(kv_cmd_t), i, C.POINTER(i)]
         L.kv_offload_pack.argtypes = [vp, i, i, C.POINTER(kv_view_t), i, i, i, vp, C.c_size_t, vp]
         L.kv_reload_unpack.argtypes = [vp, i, i, vp, C.c_size_t, C.POINTER(kv_view_t), i, i, i, vp]
         L.kv_decode_attn.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp, C.c_size_t, vp]
@@ -234,6 +235,17 @@ def kv_plan_chunk_cmds(plan: Plan, layer: int, kind: int, seq: int, chunk_tokens
     return list(arr[:n.value])
 
 
+def kv_plan_range_cmds(plan: Plan, layer: int, kind: int, seq: int, tok0: int, ntok: int,
+                       mdts_bytes: int = 0) -> List[kv_cmd_t]:
+    n = C.c_int()
+    _check(lib().kv_plan_range_cmds(plan.handle, layer, kind, seq, tok0, ntok, mdts_bytes, None, 0, C.byref(n)),
+           "kv_plan_range_cmds")
+    arr = (kv_cmd_t * max(1, n.value))()
+    _check(lib().kv_plan_range_cmds(plan.handle, layer, kind, seq, tok0, ntok, mdts_bytes, arr, n.value,
+                                    C.byref(n)), "kv_plan_range_cmds")
+    return list(arr[:n.value])
+
+
 # ------------------------------------------------------------------------------------------ views
 class View:
     """kv_view_t plus the Python objects that keep its host arrays and device tensors alive."""
@@ -330,7 +342,8 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
                     span_chunks: int = 0, host_workers: int = 0, time_kernels: bool = False,
                     copy_streams: int = 0, d2h_mode: int = KV_COPY_AUTO, h2d_mode: int = KV_COPY_AUTO,
                     serialize: bool = False, attn_from_extent: bool = False,
-                    order_pagecache: int = KV_ORDER_CROSS, order_direct: int = KV_ORDER_CROSS) -> kv_pipe_stats_t:
+                    order_pagecache: int = KV_ORDER_CROSS, order_direct: int = KV_ORDER_CROSS,
+                    max_cmd_bytes: int = 0) -> kv_pipe_stats_t:
     """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array."""
     def host(buf):
         if buf is None:
@@ -349,7 +362,7 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
         keep = (qa, oa)
     opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0)
                           | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0), copy_streams,
-                          d2h_mode, h2d_mode, order_pagecache, order_direct)
+                          d2h_mode, h2d_mode, order_pagecache, order_direct, max_cmd_bytes)
     st = kv_pipe_stats_t()
     rc = lib().kv_pipeline_run(plan.handle, direction, layer_begin, layer_end, view.ref(), rp, rb, pp, pb,
                                chunk_tokens, depth, C.byref(attn) if attn is not None else None, C.byref(opts),

@@ -321,7 +321,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // Engine defaults by measurement: H2D is fastest as hipMemcpyAsync over four streams at every chunk
     // size; D2H is fastest as hipMemcpyAsync over up to four streams for commands of 8 MiB and more, and
     // of 2 MiB and more when four may be in flight; as the copy kernel over two streams otherwise.
-    const uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
+    uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
+    uint64_t cmd_limit = UINT64_MAX;  // Eq. 7 on the caller's transfer-size limit
+    if (opts && opts->max_cmd_bytes) {
+        cmd_limit = opts->max_cmd_bytes / (uint64_t)p->sector * (uint64_t)p->sector;
+        if (cmd_limit == 0) return KV_EINVAL;
+        cmd_bytes = std::min(cmd_bytes, cmd_limit);
+    }
     const bool d2h_big = cmd_bytes >= (8ull << 20) || (cmd_bytes >= (2ull << 20) && depth >= 4);
     const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && !d2h_big);
     const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;
@@ -413,7 +419,14 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                     ch.first = ch.last = false;
                     const uint64_t host_cap = ext.path == KV_PATH_DIRECT ? region_bytes : pageable_bytes;
                     if (ch.host_off + ch.bytes > host_cap) return KV_ENOSPC;
-                    u.chunks.push_back(ch);
+                    // transfer-size limit: Eq. 8-11 once more on the chunk's own request
+                    for (uint64_t done = 0; done < ch.bytes; done += cmd_limit) {
+                        Chunk part = ch;
+                        part.host_off += done;
+                        part.stage_off += done;
+                        part.bytes = std::min(cmd_limit, ch.bytes - done);
+                        u.chunks.push_back(part);
+                    }
                 }
             }
         }

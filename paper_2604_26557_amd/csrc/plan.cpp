@@ -84,6 +84,42 @@ int chunk_cmds(const kv_plan *p, int layer, int kind, int seq, int chunk_tokens,
     return KV_OK;
 }
 
+int range_cmds(const kv_plan *p, int layer, int kind, int seq, int tok0, int ntok, uint64_t mdts_bytes,
+               std::vector<kv_cmd_t> *out)
+{
+    out->clear();
+    if (layer < 0 || layer >= p->L) return KV_ERANGE;
+    if (kind != KV_K && kind != KV_V) return KV_EINVAL;
+    RowRange r;
+    int rc = resolve_rows(p, seq, tok0, ntok, &r);  // Alg. 2: the request <slba*, req_bytes>
+    if (rc != KV_OK) return rc;
+    const uint64_t sec = (uint64_t)p->sector;
+    // Eq. 7: the largest sector multiple within the transfer-size limit
+    const uint64_t chunk_bytes = mdts_bytes == 0 ? (uint64_t)p->chunk_tokens * p->row_bytes : mdts_bytes / sec * sec;
+    if (chunk_bytes == 0) return KV_EINVAL;
+    const kv_extent_t &e = p->ext[2 * layer + kind];
+    const uint64_t first = (e.path == KV_PATH_DIRECT ? e.lba_start : e.file_off / sec) + (r.sub_off + r.byte_off) / sec;
+    const uint64_t n_chunks = ceil_div(r.req_bytes, chunk_bytes);  // Eq. 8
+    const uint64_t n_max_blocks = chunk_bytes / sec;
+    const uint64_t n_total = r.req_bytes / sec;
+    out->reserve(n_chunks);
+    for (uint64_t N = 1; N <= n_chunks; ++N) {
+        const uint64_t remains = n_total - (N - 1) * n_max_blocks;
+        const uint64_t blocks = std::min(n_max_blocks, remains);
+        kv_cmd_t c;
+        c.slba = first + (N - 1) * n_max_blocks;  // Eq. 9
+        c.nlb = (uint32_t)(blocks - 1);           // Eq. 10, 0-based
+        c.buf_off = (N - 1) * chunk_bytes;        // Eq. 11
+        // token rows the command's payload bytes touch
+        const uint64_t b0 = c.buf_off, b1 = std::min(c.buf_off + blocks * sec, r.payload);
+        c.tok0 = (uint32_t)((uint64_t)tok0 + b0 / p->row_bytes);
+        c.ntok = b1 > b0 ? (uint32_t)((b1 - 1) / p->row_bytes - b0 / p->row_bytes + 1) : 0;
+        c.reserved = 0;
+        out->push_back(c);
+    }
+    return KV_OK;
+}
+
 }  // namespace kvb
 
 using namespace kvb;
@@ -226,6 +262,18 @@ extern "C" int kv_plan_chunk_cmds(const kv_plan_t *p, int layer, int kind, int s
     return KV_OK;
 }
 
+extern "C" int kv_plan_range_cmds(const kv_plan_t *p, int layer, int kind, int seq, int tok0, int ntok,
+                                  uint64_t mdts_bytes, kv_cmd_t *out, int cap, int *n)
+{
+    if (!p || !n || cap < 0 || (cap > 0 && !out)) return KV_EINVAL;
+    std::vector<kv_cmd_t> v;
+    int rc = range_cmds(p, layer, kind, seq, tok0, ntok, mdts_bytes, &v);
+    if (rc != KV_OK) return rc;
+    *n = (int)v.size();
+    for (int i = 0; i < (int)v.size() && i < cap; ++i) out[i] = v[i];
+    return KV_OK;
+}
+
 extern "C" int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, int32_t n_threads, int64_t m_pin,
                          int64_t *m_star, int64_t *b_pc)
 {
@@ -319,4 +367,4 @@ extern "C" const char *kv_strerror(int code)
     }
 }
 
-extern "C" int kv_abi_version(void) { return 1; }
+extern "C" int kv_abi_version(void) { return 2; }

@@ -53,6 +53,8 @@ inline uint64_t extent_host_off(const kv_plan *p, int n)
 }
 
 int chunk_cmds(const kv_plan *p, int layer, int kind, int seq, int chunk_tokens, std::vector<kv_cmd_t> *out);
+int range_cmds(const kv_plan *p, int layer, int kind, int seq, int tok0, int ntok, uint64_t mdts_bytes,
+               std::vector<kv_cmd_t> *out);
 
 void set_hip_error(int e);
 

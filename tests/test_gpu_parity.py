@@ -417,6 +417,39 @@ def test_pipeline_layer_subrange_and_other_chunk_size(case):
     assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
 
 
+@pytest.mark.parametrize("span_chunks,limit_sectors", [(0, 1), (0, 3), (2, 5)])
+def test_pipeline_transfer_size_limit(case, span_chunks, limit_sectors):
+    """A command-size limit (Eq. 7 on a device's maximum transfer size) splits every chunk into commands of at
+    most that many whole sectors: same bytes on the host and back, and the command count of Eq. 8 per chunk."""
+    cfg, r = case.cfg, case.ref
+    FILL = 0xA7
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    sec = r.lba_size
+    limit = limit_sectors * sec + sec // 2          # not a sector multiple: aligned down
+    kw = dict(depth=3, span_chunks=span_chunks, max_cmd_bytes=limit)
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, **kw)
+    want_region, want_arena = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    nseq = len(case.lens) if r.per_seq else 1
+    n_cmds = 0
+    for layer in range(cfg.n_layers):
+        for kind in (0, 1):
+            for b in range(nseq):
+                for c in kv.kv_plan_chunk_cmds(case.plan, layer, kind, b):
+                    n_cmds += -(-(c.nlb + 1) // limit_sectors)
+    assert st.n_chunks == n_cmds and st.max_in_flight <= 3
+    k_new, v_new = case.blank_like_source()
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, cfg.n_layers, case.make_view(k_new, v_new), region, arena, **kw)
+    assert st.n_chunks == n_cmds
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=3,
+                           max_cmd_bytes=sec - 1)
+    assert e.value.code == kv.KV_EINVAL
+
+
 def test_pipeline_argument_errors(case):
     cfg, r = case.cfg, case.ref
     region = pinned_bytes(r.region_bytes, 0)

@@ -202,13 +202,24 @@ def test_mdts_arithmetic(paper_sizes):
     req = paper_sizes["prefill_write_bytes"]
     for dev, n_max, n_cmds in (("ssd_a", 64, 512), ("ssd_b", 4096, 64)):
         lba, mdts = paper_sizes[dev + "_lba"], paper_sizes[dev + "_mdts"]
-        chunk = (mdts // lba) * lba                            # Eq. 7 align_down
+        chunk = o.chunk_size(mdts, lba)                        # Eq. 7 align_down
+        assert chunk == n_max * lba == mdts                    # both devices' MDTS are LBA multiples
         cmds = o.chunk_cmds(2048, req, chunk, lba)
         assert len(cmds) == n_cmds
         assert all(nlb == n_max - 1 for _, nlb, _ in cmds)     # 0-based block count
         assert [c[0] for c in cmds] == [2048 + i * n_max for i in range(n_cmds)]
         assert [c[2] for c in cmds] == [i * chunk for i in range(n_cmds)]
         assert sum(nlb + 1 for _, nlb, _ in cmds) * lba == req
+
+
+def test_chunk_size_aligns_down():
+    # Eq. 7 on sizes that are not LBA multiples: the largest multiple not above MDTS
+    assert o.chunk_size(1000, 512) == 512
+    assert o.chunk_size(511, 512) == 0
+    assert o.chunk_size(4096 * 7 + 4095, 4096) == 4096 * 7
+    for mdts in range(0, 5000, 37):
+        c = o.chunk_size(mdts, 512)
+        assert c % 512 == 0 and c <= mdts < c + 512
 
 
 def test_chunk_cmds_ragged_tail():

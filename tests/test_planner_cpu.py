@@ -34,7 +34,7 @@ def test_header_symbols_exported():
     lib = kv.lib()
     for name in declared:
         assert hasattr(lib, name)
-    assert lib.kv_abi_version() == 1
+    assert lib.kv_abi_version() == 2
 
 
 @pytest.mark.parametrize("idx", range(5))
@@ -114,6 +114,58 @@ def test_chunk_cmds_other_chunk_sizes():
     with pytest.raises(kv.KVError) as e:
         kv.kv_plan_chunk_cmds(p, 2, 1, 0, 3)
     assert e.value.code == kv.KV_EALIGN
+
+
+@pytest.mark.parametrize("idx", [0, 1, 3])
+def test_range_cmds_with_transfer_limit_match_oracle(idx):
+    """Alg. 2 on a token range, then Eq. 7-11 with the chunk size drawn from a transfer-size limit."""
+    cfg = W.CONFIGS[idx]
+    if idx == 3:
+        cfg = W.shrink(cfg, n_layers=3, len_range=(100, 700))
+    p, ref, lens = _plans(cfg)
+    sec, rb = ref.lba_size, ref.row_bytes
+    rng = np.random.default_rng(100 + idx)
+    nseq = len(lens) if ref.per_seq else 1
+    n_ok = 0
+    for layer, kind in ((0, 0), (cfg.n_layers - 1, 1)):
+        n = 2 * layer + kind
+        for b in range(nseq):
+            cap = lens[b]
+            ranges = [(0, cap), (cap - 1, 1)] + [(int(rng.integers(0, cap)), int(rng.integers(1, cap + 1))) for _ in range(30)]
+            for tok0, ntok in ranges:
+                want = _expected_translate(ref, n, b, tok0, ntok)
+                for mdts in (0, sec, sec + 1, 3 * sec - 1, 5 * rb + 3, 256 * 1024, 1 << 21):
+                    if want[0] != o.OK:
+                        with pytest.raises(kv.KVError) as e:
+                            kv.kv_plan_range_cmds(p, layer, kind, b, tok0, ntok, mdts)
+                        assert e.value.code == want[0]
+                        continue
+                    chunk = o.chunk_size(mdts, sec) if mdts else cfg.chunk_tokens * rb
+                    want_cmds = o.chunk_cmds(want[1], want[2], chunk, sec)
+                    got = kv.kv_plan_range_cmds(p, layer, kind, b, tok0, ntok, mdts)
+                    assert [(c.slba, c.nlb, c.buf_off) for c in got] == want_cmds
+                    # rows named by each command: those its payload bytes touch
+                    for c in got:
+                        lo, hi = c.buf_off, min(c.buf_off + (c.nlb + 1) * sec, ntok * rb)
+                        rows = set(range(tok0 + lo // rb, tok0 + -(-hi // rb))) if hi > lo else set()
+                        assert set(range(c.tok0, c.tok0 + c.ntok)) == rows
+                    n_ok += 1
+    assert n_ok > 50
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_plan_range_cmds(p, 0, 0, 0, 0, lens[0], sec - 1)   # limit below one sector
+    assert e.value.code == kv.KV_EINVAL
+
+
+def test_range_cmds_paper_devices(paper_sizes):
+    """The two devices' MDTS and LBA sizes on a 128 MiB request: 512 and 64 commands (Sec. V-A)."""
+    for dev, n_max, n_cmds in (("ssd_a", 64, 512), ("ssd_b", 4096, 64)):
+        lba, mdts = paper_sizes[dev + "_lba"], paper_sizes[dev + "_mdts"]
+        rows = paper_sizes["prefill_write_bytes"] // (32 * 32 * 128 * 2)   # B=32, H=32, D=128, 16-bit: 512 rows
+        p = kv.kv_layout_plan(1, 32, 32, 128, [rows] * 32, kv.KV_F16, lba, 2, kv.KV_TOKEN_MAJOR, 2048,
+                              kv.KV_UNBOUNDED, 0, kv.KV_UNBOUNDED)
+        cmds = kv.kv_plan_range_cmds(p, 0, 0, 0, 0, rows, mdts)
+        assert len(cmds) == n_cmds and all(c.nlb == n_max - 1 for c in cmds)
+        assert [c.slba for c in cmds] == [2048 + i * n_max for i in range(n_cmds)]
 
 
 def test_pagecache_path_addresses_are_arena_sectors():
