@@ -275,6 +275,122 @@ int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, si
     return KV_OK;
 }
 
+struct Schedule {
+    std::vector<Span> spans;    // kernel launches / staging-slot fills, in issue order
+    std::vector<Chunk> chunks;  // chunk commands, in issue order
+    uint64_t slot_bytes = 0;    // largest span image, rounded up to 4 KiB
+    long long group_last[2] = {-1, -1};
+};
+
+// Spans and chunk commands of layers [layer_begin, layer_end): Eq. 7-11 per tensor (and sequence) with C token
+// rows per chunk, each chunk cut once more under the transfer-size limit, emitted in the overlap order of the
+// layer's path group.
+int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C, int span_chunks, int order_pc,
+                   int order_direct, uint64_t cmd_limit, uint64_t region_bytes, uint64_t pageable_bytes, Schedule *out)
+{
+    std::vector<Span> &spans = out->spans;
+    std::vector<Chunk> &chunks = out->chunks;
+    std::vector<kv_cmd_t> cmds;
+    const uint64_t sec = (uint64_t)p->sector;
+    const uint64_t image = p->tensor_blocks * sec;
+    // Units: a span with its chunk commands.  Per layer the K units and the V units are emitted either one
+    // tensor after the other (KV_ORDER_CROSS: V's storage-side hop runs while K's transfers are in flight)
+    // or alternating (KV_ORDER_INTRA: both tensors' hops proceed side by side) -- the two overlap
+    // strategies of Sec. IV-C.
+    struct Unit { Span span; std::vector<Chunk> chunks; };
+    for (int l = layer_begin; l < layer_end; ++l) {
+        const int order = l < p->n1 ? order_pc : order_direct;
+        // Whole-extent spans: K and V of a layer share one launch while the pair stays within 256 MiB
+        // (measured: pairing gains ~5 % at 64 MiB tensors and loses ~10 % at 256 MiB tensors), or when
+        // their chunks alternate.
+        const bool pair = span_chunks == 0 && (2 * image <= (256ull << 20) || order == KV_ORDER_INTRA);
+        std::vector<Unit> units[2];
+        for (int kind = 0; kind < 2; ++kind) {
+            const kv_extent_t &ext = p->ext[2 * l + kind];
+            const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
+            if (span_chunks == 0) {
+                Unit u;
+                u.span = pair ? Span{l, KV_KV, KV_SEQ_ALL, 0, 0, 2 * image, ext.path, false}
+                              : Span{l, kind, KV_SEQ_ALL, 0, 0, image, ext.path, false};
+                units[kind].push_back(u);
+            }
+            for (int b = 0; b < nseq; ++b) {
+                int rc = kvb::chunk_cmds(p, l, kind, b, (int)C, &cmds);
+                if (rc != KV_OK) return rc;
+                for (size_t i = 0; i < cmds.size(); ++i) {
+                    const kv_cmd_t &c = cmds[i];
+                    if (span_chunks > 0 && i % (size_t)span_chunks == 0) {
+                        const size_t j = std::min(cmds.size(), i + (size_t)span_chunks) - 1;
+                        Unit u;
+                        u.span = Span{l, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false};
+                        for (size_t k = i; k <= j; ++k) u.span.bytes += ((uint64_t)cmds[k].nlb + 1) * sec;
+                        units[kind].push_back(u);
+                    }
+                    Unit &u = units[kind].back();
+                    Chunk ch;
+                    ch.host_off = c.slba * sec;
+                    ch.bytes = ((uint64_t)c.nlb + 1) * sec;
+                    ch.span = -1;
+                    ch.stage_off = span_chunks == 0 ? (pair ? (uint64_t)kind * image : 0) + p->seq_base[b] * sec + c.buf_off
+                                                    : c.buf_off - (uint64_t)u.span.tok0 * p->row_bytes;
+                    ch.first = ch.last = false;
+                    const uint64_t host_cap = ext.path == KV_PATH_DIRECT ? region_bytes : pageable_bytes;
+                    if (ch.host_off + ch.bytes > host_cap) return KV_ENOSPC;
+                    // transfer-size limit: Eq. 8-11 once more on the chunk's own request
+                    for (uint64_t done = 0; done < ch.bytes; done += cmd_limit) {
+                        Chunk part = ch;
+                        part.host_off += done;
+                        part.stage_off += done;
+                        part.bytes = std::min(cmd_limit, ch.bytes - done);
+                        u.chunks.push_back(part);
+                    }
+                }
+            }
+        }
+        auto emit_span = [&](const Span &sp) { spans.push_back(sp); return (int)spans.size() - 1; };
+        auto emit_chunk = [&](Chunk ch, int span) { ch.span = span; chunks.push_back(ch); };
+        if (pair) {
+            // one span; its K commands and V commands in the chosen order
+            const int si = emit_span(units[0][0].span);
+            const std::vector<Chunk> &ck = units[0][0].chunks, &cv = units[1][0].chunks;
+            if (order == KV_ORDER_INTRA) {
+                for (size_t i = 0; i < std::max(ck.size(), cv.size()); ++i) {
+                    if (i < ck.size()) emit_chunk(ck[i], si);
+                    if (i < cv.size()) emit_chunk(cv[i], si);
+                }
+            } else {
+                for (const Chunk &c : ck) emit_chunk(c, si);
+                for (const Chunk &c : cv) emit_chunk(c, si);
+            }
+        } else if (order == KV_ORDER_INTRA) {
+            for (size_t i = 0; i < std::max(units[0].size(), units[1].size()); ++i)
+                for (int kind = 0; kind < 2; ++kind)
+                    if (i < units[kind].size()) {
+                        const int si = emit_span(units[kind][i].span);
+                        for (const Chunk &c : units[kind][i].chunks) emit_chunk(c, si);
+                    }
+        } else {
+            for (int kind = 0; kind < 2; ++kind)
+                for (const Unit &u : units[kind]) {
+                    const int si = emit_span(u.span);
+                    for (const Chunk &c : u.chunks) emit_chunk(c, si);
+                }
+        }
+        if (!spans.empty()) spans.back().last_of_layer = true;
+    }
+    // last chunk command of each path group (for the per-group throughput figures)
+    long long *group_last = out->group_last;
+    for (size_t i = 0; i < chunks.size(); ++i) group_last[spans[chunks[i].span].path == KV_PATH_PAGECACHE ? 0 : 1] = (long long)i;
+    for (size_t i = 0; i < chunks.size(); ++i) {
+        chunks[i].first = i == 0 || chunks[i - 1].span != chunks[i].span;
+        chunks[i].last = i + 1 == chunks.size() || chunks[i + 1].span != chunks[i].span;
+    }
+    uint64_t slot_bytes = 0;
+    for (const Span &s : spans) slot_bytes = std::max(slot_bytes, s.bytes);
+    out->slot_bytes = kvb::round_up(slot_bytes, 4096);
+    return KV_OK;
+}
+
 inline void spin_until_zero(std::atomic<int> &a)
 {
     int spins = 0;
@@ -370,106 +486,17 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (span_chunks > 0 && len != p->cap[b]) return KV_EINVAL;
     }
 
-    // ---- build the span and chunk lists -------------------------------------------------------
-    std::vector<Span> spans;
-    std::vector<Chunk> chunks;
-    std::vector<kv_cmd_t> cmds;
-    uint64_t slot_bytes = 0;
+    Schedule sched;
+    {
+        int rc = build_schedule(p, layer_begin, layer_end, C, span_chunks, order_pc, order_direct, cmd_limit, region_bytes,
+                                pageable_bytes, &sched);
+        if (rc != KV_OK) return rc;
+    }
+    const std::vector<Span> &spans = sched.spans;
+    const std::vector<Chunk> &chunks = sched.chunks;
+    const uint64_t slot_bytes = sched.slot_bytes;
+    const long long *group_last = sched.group_last;
     const uint64_t image = p->tensor_blocks * sec;
-    // Units: a span with its chunk commands.  Per layer the K units and the V units are emitted either one
-    // tensor after the other (KV_ORDER_CROSS: V's storage-side hop runs while K's transfers are in flight)
-    // or alternating (KV_ORDER_INTRA: both tensors' hops proceed side by side) -- the two overlap
-    // strategies of Sec. IV-C.
-    struct Unit { Span span; std::vector<Chunk> chunks; };
-    for (int l = layer_begin; l < layer_end; ++l) {
-        const int order = l < p->n1 ? order_pc : order_direct;
-        // Whole-extent spans: K and V of a layer share one launch while the pair stays within 256 MiB
-        // (measured: pairing gains ~5 % at 64 MiB tensors and loses ~10 % at 256 MiB tensors), or when
-        // their chunks alternate.
-        const bool pair = span_chunks == 0 && (2 * image <= (256ull << 20) || order == KV_ORDER_INTRA);
-        std::vector<Unit> units[2];
-        for (int kind = 0; kind < 2; ++kind) {
-            const kv_extent_t &ext = p->ext[2 * l + kind];
-            const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
-            if (span_chunks == 0) {
-                Unit u;
-                u.span = pair ? Span{l, KV_KV, KV_SEQ_ALL, 0, 0, 2 * image, ext.path, false}
-                              : Span{l, kind, KV_SEQ_ALL, 0, 0, image, ext.path, false};
-                units[kind].push_back(u);
-            }
-            for (int b = 0; b < nseq; ++b) {
-                int rc = kvb::chunk_cmds(p, l, kind, b, (int)C, &cmds);
-                if (rc != KV_OK) return rc;
-                for (size_t i = 0; i < cmds.size(); ++i) {
-                    const kv_cmd_t &c = cmds[i];
-                    if (span_chunks > 0 && i % (size_t)span_chunks == 0) {
-                        const size_t j = std::min(cmds.size(), i + (size_t)span_chunks) - 1;
-                        Unit u;
-                        u.span = Span{l, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false};
-                        for (size_t k = i; k <= j; ++k) u.span.bytes += ((uint64_t)cmds[k].nlb + 1) * sec;
-                        units[kind].push_back(u);
-                    }
-                    Unit &u = units[kind].back();
-                    Chunk ch;
-                    ch.host_off = c.slba * sec;
-                    ch.bytes = ((uint64_t)c.nlb + 1) * sec;
-                    ch.span = -1;
-                    ch.stage_off = span_chunks == 0 ? (pair ? (uint64_t)kind * image : 0) + p->seq_base[b] * sec + c.buf_off
-                                                    : c.buf_off - (uint64_t)u.span.tok0 * p->row_bytes;
-                    ch.first = ch.last = false;
-                    const uint64_t host_cap = ext.path == KV_PATH_DIRECT ? region_bytes : pageable_bytes;
-                    if (ch.host_off + ch.bytes > host_cap) return KV_ENOSPC;
-                    // transfer-size limit: Eq. 8-11 once more on the chunk's own request
-                    for (uint64_t done = 0; done < ch.bytes; done += cmd_limit) {
-                        Chunk part = ch;
-                        part.host_off += done;
-                        part.stage_off += done;
-                        part.bytes = std::min(cmd_limit, ch.bytes - done);
-                        u.chunks.push_back(part);
-                    }
-                }
-            }
-        }
-        auto emit_span = [&](const Span &sp) { spans.push_back(sp); return (int)spans.size() - 1; };
-        auto emit_chunk = [&](Chunk ch, int span) { ch.span = span; chunks.push_back(ch); };
-        if (pair) {
-            // one span; its K commands and V commands in the chosen order
-            const int si = emit_span(units[0][0].span);
-            const std::vector<Chunk> &ck = units[0][0].chunks, &cv = units[1][0].chunks;
-            if (order == KV_ORDER_INTRA) {
-                for (size_t i = 0; i < std::max(ck.size(), cv.size()); ++i) {
-                    if (i < ck.size()) emit_chunk(ck[i], si);
-                    if (i < cv.size()) emit_chunk(cv[i], si);
-                }
-            } else {
-                for (const Chunk &c : ck) emit_chunk(c, si);
-                for (const Chunk &c : cv) emit_chunk(c, si);
-            }
-        } else if (order == KV_ORDER_INTRA) {
-            for (size_t i = 0; i < std::max(units[0].size(), units[1].size()); ++i)
-                for (int kind = 0; kind < 2; ++kind)
-                    if (i < units[kind].size()) {
-                        const int si = emit_span(units[kind][i].span);
-                        for (const Chunk &c : units[kind][i].chunks) emit_chunk(c, si);
-                    }
-        } else {
-            for (int kind = 0; kind < 2; ++kind)
-                for (const Unit &u : units[kind]) {
-                    const int si = emit_span(u.span);
-                    for (const Chunk &c : u.chunks) emit_chunk(c, si);
-                }
-        }
-        if (!spans.empty()) spans.back().last_of_layer = true;
-    }
-    // last chunk command of each path group (for the per-group throughput figures)
-    long long group_last[2] = {-1, -1};
-    for (size_t i = 0; i < chunks.size(); ++i) group_last[spans[chunks[i].span].path == KV_PATH_PAGECACHE ? 0 : 1] = (long long)i;
-    for (size_t i = 0; i < chunks.size(); ++i) {
-        chunks[i].first = i == 0 || chunks[i - 1].span != chunks[i].span;
-        chunks[i].last = i + 1 == chunks.size() || chunks[i + 1].span != chunks[i].span;
-    }
-    for (const Span &s : spans) slot_bytes = std::max(slot_bytes, s.bytes);
-    slot_bytes = kvb::round_up(slot_bytes, 4096);
     const size_t n_slots = span_chunks == 0 ? 4 : std::max<size_t>(4, (size_t)depth);
 
     size_t ws_bytes = 0;

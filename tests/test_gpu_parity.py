@@ -520,6 +520,13 @@ def test_decode_append(cfg):
     K, V = case.k_cpu[0], case.v_cpu[0]
     want = o.attention(case.source(K), o.u16(K), o.u16(V), o.u16(q), cfg.dtype == W.BF16, lens, cfg.n_q_heads)
     _attn_check(out, want)
+    # the next decode step's reload (storage -> staged extent images -> attention) sees the appended rows too
+    k_new, v_new = case.blank_like_source()
+    qd = [W.query(cfg, l, "cpu").cuda() for l in range(cfg.n_layers)]
+    outs = [torch.zeros_like(out) for _ in range(cfg.n_layers)]
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, case.make_view(k_new, v_new, lens), region, arena,
+                       depth=2, q_layers=qd, out_layers=outs, attn_from_extent=True)
+    _attn_check(outs[0], want)
     # capacity is a hard bound
     with pytest.raises(kv.KVError) as e:
         kv.kv_append_tokens(case.plan, 0, cfg.n_layers, case.make_view(case.k, case.v, [n + 1 for n in lens]), region, arena)
