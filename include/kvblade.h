@@ -290,7 +290,8 @@ int kv_reload_unpack(const kv_plan_t *plan, int layer, int kind, const void *src
  * kv_decode_attn -- one decode-attention step of one layer over resident KV (Sec. II-A: similarity of
  * the query with the keys weights the values): out[b,hq,:] = softmax_j(q[b,hq,:].K[b,h,j,:] / sqrt(D))
  * V[b,h,j,:], j in [0, len_b), h = hq / (H_q/H); fp32 accumulation; split-K over tokens with a
- * combine pass.  len_b = kv->seq_lens_dev (device) with kv->seq_lens_host as its host mirror; a
+ * combine pass.  len_b = kv->seq_lens_dev (device) with kv->seq_lens_host as its host mirror (both must
+ * hold the same values: a batch whose sequences all have one length takes it from the host mirror at launch); a
  * sequence of length 0 yields zeros.
  * q: device [B,H_q,D] 16-bit, 16-byte aligned; out: device [B,H_q,D] fp32 or 16-bit (out_dtype);
  * workspace: device, >= kv_decode_attn_workspace() bytes (else KV_ENOSPC); n_splits 0 = choose.

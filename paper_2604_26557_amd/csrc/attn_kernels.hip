@@ -29,6 +29,7 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
@@ -40,6 +41,7 @@ struct AttnParams {
     const u32x4 *K, *V;    // attention-side buffers of the layer
     const u32x4 *q;        // [B, Hq, D]
     const int *seq_lens;   // device [B]
+    int len_uniform;       // >= 0: every sequence has this length (saves the first dependent load); -1: read seq_lens
     float *part_acc;       // [B, Hq, n_splits, D]
     float *part_ml;        // [B, Hq, n_splits, 2]
     long long sb, sh, ss;  // strided layout, in 16-byte vectors
@@ -127,7 +129,7 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
     const int g_own = n % GT;
     const int lr = n % LPRV, half = n / LPRV;
 
-    const int len = min(p.seq_lens[b], p.max_len);
+    const int len = p.len_uniform >= 0 ? p.len_uniform : min(p.seq_lens[b], p.max_len);
     const int t_begin = min(len, split * p.split_tokens);
     const int t_end = min(len, t_begin + p.split_tokens);
 
@@ -239,7 +241,12 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
         }
     }
 
-    // ---- every lane gets (m, l) of all heads of its row group; then row groups are merged
+    // ---- merge: every (wavefront, row group) is one softmax state (m, l, acc[D]) per head.  The states go
+    // to LDS as they are (for D = 256 row-group pairs are first merged by one shuffle round, to halve the
+    // LDS footprint), their weights exp2(m - M) are computed once per (state, head), and the workgroup then
+    // forms the weighted sums: far fewer instructions than merging in registers through shuffles.
+    constexpr int SR = D == 256 ? 1 : 0;       // shuffle rounds before LDS
+    constexpr int NS = kWaves * (4 >> SR);     // states per head in LDS
     float mg[GT], lg[GT];
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
@@ -253,7 +260,8 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
             for (int e = 0; e < AE; ++e) acc[g][e] += __shfl_xor(acc[g][e], 8);
     }
 #pragma unroll
-    for (int off = 16; off < 64; off <<= 1) {
+    for (int r = 0; r < SR; ++r) {
+        const int off = 16 << r;
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
             const float m2 = __shfl_xor(mg[g], off), l2 = __shfl_xor(lg[g], off);
@@ -264,35 +272,48 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
         }
     }
 
-    // ---- merge the wavefronts through LDS
-    __shared__ float sh_acc[kWaves][GT][D];
-    __shared__ float sh_ml[kWaves][GT][2];
-    if (tg == 0 && half == 0) {
+    __shared__ __attribute__((aligned(16))) float sh_acc[NS][GT][D];
+    __shared__ float sh_ml[NS][GT][2];
+    __shared__ float sh_w[NS][GT];
+    __shared__ float sh_ML[GT][2];
+    const int state = wave * (4 >> SR) + (tg >> SR);
+    if ((tg & ((1 << SR) - 1)) == 0 && half == 0) {
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
 #pragma unroll
-            for (int w = 0; w < NV; ++w)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) sh_acc[wave][g][(lr + w * LPRV) * 8 + e] = acc[g][w * 8 + e];
-            if (n == 0) { sh_ml[wave][g][0] = mg[g]; sh_ml[wave][g][1] = lg[g]; }
+            for (int w = 0; w < NV; ++w) {
+                float *dst = &sh_acc[state][g][(lr + w * LPRV) * 8];
+                *(f32x4 *)dst = f32x4{acc[g][w * 8 + 0], acc[g][w * 8 + 1], acc[g][w * 8 + 2], acc[g][w * 8 + 3]};
+                *(f32x4 *)(dst + 4) = f32x4{acc[g][w * 8 + 4], acc[g][w * 8 + 5], acc[g][w * 8 + 6], acc[g][w * 8 + 7]};
+            }
+            if (n == 0) { sh_ml[state][g][0] = mg[g]; sh_ml[state][g][1] = lg[g]; }
         }
+    }
+    __syncthreads();
+    if (threadIdx.x < GT) {  // one thread per head: maximum, weights, denominator
+        const int g = threadIdx.x;
+        float M = sh_ml[0][g][0];
+#pragma unroll
+        for (int st = 1; st < NS; ++st) M = fmaxf(M, sh_ml[st][g][0]);
+        float L = 0.f;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            const float a = exp2f(sh_ml[st][g][0] - M);
+            sh_w[st][g] = a;
+            L += sh_ml[st][g][1] * a;
+        }
+        sh_ML[g][0] = M;
+        sh_ML[g][1] = L;
     }
     __syncthreads();
     for (int idx = threadIdx.x; idx < GT * D; idx += kThreads) {
         const int g = idx / D, d = idx - g * D;
-        float M = sh_ml[0][g][0];
+        float A = 0.f;
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sh_ml[w][g][0]);
-        float L = 0.f, A = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float a = exp2f(sh_ml[w][g][0] - M);
-            L += sh_ml[w][g][1] * a;
-            A += sh_acc[w][g][d] * a;
-        }
+        for (int st = 0; st < NS; ++st) A = fmaf(sh_acc[st][g][d], sh_w[st][g], A);
         const long long o = ((long long)b * p.Hq + hq0 + g) * p.n_splits + split;
         p.part_acc[o * D + d] = A;
-        if (d == 0) { p.part_ml[o * 2] = M; p.part_ml[o * 2 + 1] = L; }
+        if (d == 0) { p.part_ml[o * 2] = sh_ML[g][0]; p.part_ml[o * 2 + 1] = sh_ML[g][1]; }
     }
 }
 
@@ -304,11 +325,14 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
     return (unsigned short)(u >> 16);
 }
 
-// out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup of 256 threads per (hq, b).  The split weights
-// exp2(m_s - M) are computed once, in parallel over the splits, and kept in LDS.  Threads are then laid
-// out as (d, split group): group k sums splits k, k+NG, ... of column d with independent loads, and
-// the NG partial sums are added through LDS.
+// out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup of 256 threads per (hq, b, 32 output columns): threads are
+// (column, split group), eight groups, group k summing splits k, k+8, ...  The loads of a thread's first
+// kCombinePrefetch partial rows do not depend on the split weights, so they are issued first and the two
+// memory latencies (weights' inputs, partial rows) overlap.  The weights exp2(m_s - M) go to LDS.
 constexpr int kCombineThreads = 256;
+constexpr int kCombineCols = 32;
+constexpr int kCombineGroups = kCombineThreads / kCombineCols;
+constexpr int kCombinePrefetch = 8;
 constexpr int kMaxSplits = 1024;
 
 __global__ void __launch_bounds__(kCombineThreads)
@@ -316,53 +340,73 @@ kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restri
                        void *__restrict__ out, int Hq, int D, int n_splits, int out_mode)
 {
     __shared__ float w[kMaxSplits];
-    __shared__ float red[kCombineThreads / 64];
-    __shared__ float colsum[kCombineThreads];
-    __shared__ float sh_M, sh_L;
-    const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    __shared__ float colsum[kCombineThreads / 64][kCombineCols];
+    const int hq = blockIdx.x, b = blockIdx.y, d = blockIdx.z * kCombineCols + (threadIdx.x & (kCombineCols - 1));
+    const int tid = threadIdx.x, lane = tid & 63, grp = tid / kCombineCols;
     const long long o = ((long long)b * Hq + hq) * n_splits;
 
-    float mx = kEmptyMax;
-    for (int s = tid; s < n_splits; s += kCombineThreads) mx = fmaxf(mx, part_ml[(o + s) * 2]);
+    float pre[kCombinePrefetch];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    __syncthreads();
-    if (tid == 0) {
-        float M = red[0];
-        for (int i = 1; i < kCombineThreads / 64; ++i) M = fmaxf(M, red[i]);
-        sh_M = M;
+    for (int i = 0; i < kCombinePrefetch; ++i) {
+        const int s = grp + i * kCombineGroups;
+        pre[i] = s < n_splits ? part_acc[(o + s) * D + d] : 0.f;
     }
-    __syncthreads();
-    const float M = sh_M;
-    float lsum = 0.f;
-    for (int s = tid; s < n_splits; s += kCombineThreads) {
-        const float a = exp2f(part_ml[(o + s) * 2] - M);
-        w[s] = a;
-        lsum += part_ml[(o + s) * 2 + 1] * a;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off);
-    __syncthreads();  // red is reused
-    if ((tid & 63) == 0) red[tid >> 6] = lsum;
-    __syncthreads();
-    if (tid == 0) {
-        float L = 0.f;
-        for (int i = 0; i < kCombineThreads / 64; ++i) L += red[i];
-        sh_L = L;
-    }
-    __syncthreads();
-    const float L = sh_L;
 
-    const int NG = kCombineThreads / D;  // D is 64, 128 or 256
-    const int d = tid % D, grp = tid / D;
-    float A = 0.f;
-#pragma unroll 8
-    for (int s = grp; s < n_splits; s += NG) A = fmaf(part_acc[(o + s) * D + d], w[s], A);
-    colsum[tid] = A;
+    // Wavefront 0 alone forms the maximum, the weights and the denominator: one load of its lanes' (m, l)
+    // pairs (two per lane cover 128 splits; a rare tail loop takes the rest), two shuffle reductions.
+    float L = 0.f;
+    if (tid < 64) {
+        float m2[2], l2[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int s = lane + 64 * i;
+            m2[i] = kEmptyMax;
+            l2[i] = 0.f;
+            if (s < n_splits) {
+                const f32x2 v = *(const f32x2 *)&part_ml[(o + s) * 2];
+                m2[i] = v[0];
+                l2[i] = v[1];
+            }
+        }
+        float mx = fmaxf(m2[0], m2[1]);
+        for (int s = lane + 128; s < n_splits; s += 64) mx = fmaxf(mx, part_ml[(o + s) * 2]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        const float M = mx;
+        float lsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int s = lane + 64 * i;
+            const float a = exp2f(m2[i] - M);
+            if (s < n_splits) w[s] = a;
+            lsum += l2[i] * a;
+        }
+        for (int s = lane + 128; s < n_splits; s += 64) {
+            const float a = exp2f(part_ml[(o + s) * 2] - M);
+            w[s] = a;
+            lsum += part_ml[(o + s) * 2 + 1] * a;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off);
+        L = lsum;
+    }
     __syncthreads();
-    if (grp == 0) {
-        for (int k = 1; k < NG; ++k) A += colsum[k * D + d];
+
+    float A = 0.f;
+#pragma unroll
+    for (int i = 0; i < kCombinePrefetch; ++i) {
+        const int s = grp + i * kCombineGroups;
+        if (s < n_splits) A = fmaf(pre[i], w[s], A);
+    }
+#pragma unroll 4
+    for (int s = grp + kCombinePrefetch * kCombineGroups; s < n_splits; s += kCombineGroups)
+        A = fmaf(part_acc[(o + s) * D + d], w[s], A);
+    A += __shfl_xor(A, 32);  // the two split groups of a wavefront
+    if (lane < kCombineCols) colsum[tid >> 6][lane] = A;
+    __syncthreads();
+    if (tid < kCombineCols) {
+#pragma unroll
+        for (int k = 1; k < kCombineThreads / 64; ++k) A += colsum[k][tid];
         const float r = L > 0.f ? A / L : 0.f;
         const long long oi = ((long long)b * Hq + hq) * D + d;
         if (out_mode == 0) ((float *)out)[oi] = r;
@@ -495,6 +539,9 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
     const int G = p->Hq / p->H, gt = pick_gt(G);
     a.K = (const u32x4 *)K; a.V = (const u32x4 *)V; a.q = (const u32x4 *)q;
     a.seq_lens = kv->seq_lens_dev;
+    a.len_uniform = max_len;
+    for (int b = 0; b < p->B; ++b)
+        if (kv->seq_lens_host[b] != max_len) a.len_uniform = -1;
     a.part_acc = (float *)workspace;
     a.part_ml = a.part_acc + (size_t)p->B * p->Hq * ns * p->D;
     a.H = p->H; a.Hq = p->Hq; a.G = G;
@@ -513,7 +560,7 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
 
     const int out_mode = out_dtype == KV_OUT_F32 ? 0 : (bf16 ? 2 : 1);
-    hipLaunchKernelGGL(kv_attn_combine_kernel, dim3((unsigned)p->Hq, (unsigned)p->B), dim3(kCombineThreads), 0,
+    hipLaunchKernelGGL(kv_attn_combine_kernel, dim3((unsigned)p->Hq, (unsigned)p->B, (unsigned)(p->D / kCombineCols)), dim3(kCombineThreads), 0,
                        st, a.part_acc, a.part_ml, out, p->Hq, p->D, ns, out_mode);
     e = hipGetLastError();
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }

@@ -232,7 +232,7 @@ def _attn_check(got: torch.Tensor, want: np.ndarray):
     assert err <= ATTN_REL_OF_MAX * scale, (err, scale)
 
 
-@pytest.mark.parametrize("n_splits", [0, 1, 3])
+@pytest.mark.parametrize("n_splits", [0, 1, 3, 70, 200])
 def test_decode_attention(case, n_splits):
     cfg = case.cfg
     max_len = max(case.lens)
