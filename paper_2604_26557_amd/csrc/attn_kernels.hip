@@ -147,19 +147,37 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
 
     const long long head_off = PAGED ? 0 : (p.seq_off ? p.seq_off[b] / 8 : (long long)b * p.sb) + (long long)h * p.sh;
     const int *tbl = PAGED ? p.table + (long long)b * p.max_blocks : nullptr;
-    // vector index of the first element of token row `row`; ok = false for a block id outside the pool
-    auto row_base = [&](int row, bool &ok) -> long long {
+    auto block_of = [&](int row) -> int { return p.bt_shift >= 0 ? (row >> p.bt_shift) : (row / p.bt); };
+    // vector index of the first element of token row `row` (paged: in pool block blk; ok = false for a block
+    // id outside the pool, which then reads block 0 and is masked)
+    auto row_base = [&](int row, int blk, bool &ok) -> long long {
         if (PAGED) {
-            const int j = p.bt_shift >= 0 ? (row >> p.bt_shift) : (row / p.bt);
-            const int slot = row - j * p.bt;
-            int blk = tbl[j];
+            const int slot = row - block_of(row) * p.bt;
             if ((unsigned)blk >= (unsigned)p.n_pool) { blk = 0; ok = false; }
             return (((long long)blk * p.H + h) * p.bt + slot) * DV;
         }
         return head_off + (long long)row * p.ss;
     };
+    // Paged layout: the block ids of one iteration's rows -- this lane's K row and the 4 tokens of its row
+    // group, per tile -- are fetched one iteration ahead, so that the table lookup is off the load chain.
+    struct Ids { int k[TI]; int t[TI][4]; };
+    auto fetch_ids = [&](int Tw, Ids &ids) {
+#pragma unroll
+        for (int ti = 0; ti < TI; ++ti) {
+            const int T0 = Tw + kTile * ti;
+            ids.k[ti] = tbl[block_of((T0 + n < t_end) ? T0 + n : t_begin)];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int tok = T0 + 4 * tg + i;
+                ids.t[ti][i] = tbl[block_of(tok < t_end ? tok : t_begin)];
+            }
+        }
+    };
+    Ids ids{};
+    const int Tw0 = t_begin + kTile * TI * wave;
+    if (PAGED && Tw0 < t_end) fetch_ids(Tw0, ids);
 
-    for (int Tw = t_begin + kTile * TI * wave; Tw < t_end; Tw += kTile * TI * kWaves) {
+    for (int Tw = Tw0; Tw < t_end; Tw += kTile * TI * kWaves) {
         // ---- loads of TI adjacent tiles: K tile in A-operand order, V rows of this row group's tokens
         u32x4 kvec[TI][NJ];
         u32x4 vvec[TI][NU][NV];
@@ -169,32 +187,30 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
             const int T0 = Tw + kTile * ti;
             bool k_ok = true;
             const int krow = (T0 + n < t_end) ? T0 + n : t_begin;  // rows past the end re-read a valid row; masked below
-            const long long kb = row_base(krow, k_ok);
+            const long long kb = row_base(krow, PAGED ? ids.k[ti] : 0, k_ok);
 #pragma unroll
             for (int j = 0; j < NJ; ++j) kvec[ti][j] = p.K[kb + 4 * j + tg];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) tok_ok[ti][i] = (T0 + 4 * tg + i) < t_end;
+            for (int i = 0; i < 4; ++i) {
+                // a token whose block id is outside the pool is not attended; every lane of the row group
+                // sees the same four ids, so they agree on the flag
+                tok_ok[ti][i] = (T0 + 4 * tg + i) < t_end;
+                if (PAGED) tok_ok[ti][i] = tok_ok[ti][i] && (unsigned)ids.t[ti][i] < (unsigned)p.n_pool;
+            }
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
                 const int i = u * TPL + half;
                 const int tok = T0 + 4 * tg + i;
                 bool ok = true;
-                const long long vb = row_base(tok < t_end ? tok : t_begin, ok);
+                const int blk = !PAGED ? 0 : (TPL == 1 ? ids.t[ti][u] : (half ? ids.t[ti][(2 * u + 1) & 3] : ids.t[ti][(2 * u) & 3]));
+                const long long vb = row_base(tok < t_end ? tok : t_begin, blk, ok);
 #pragma unroll
                 for (int w = 0; w < NV; ++w) vvec[ti][u][w] = p.V[vb + lr + w * LPRV];
-                // a token whose block id is outside the pool is not attended; every lane of the row
-                // group must agree, so the flag is taken per token, not per lane
-                if (PAGED && TPL == 1) tok_ok[ti][u] = tok_ok[ti][u] && ok;
             }
-            if (PAGED && TPL == 2) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    bool ok = true;
-                    const int tok = T0 + 4 * tg + i;
-                    (void)row_base(tok < t_end ? tok : t_begin, ok);
-                    tok_ok[ti][i] = tok_ok[ti][i] && ok;
-                }
-            }
+        }
+        if (PAGED) {
+            const int next = Tw + kTile * TI * kWaves;
+            if (next < t_end) fetch_ids(next, ids);
         }
 
 #pragma unroll
