@@ -26,9 +26,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # llama8b_32k workload (profiles/pmc_traffic_llama8b_32k.md), each counter scaled by what it reads for a
 # plain 128 MiB device-to-device copy in the same run.  Valid only for the kernel sources they were taken
 # with: the hash below covers the two kernel files, and a mismatch reports traffic as null.
-PMC_TRAFFIC = {"sha": "6989982857319810", "workload": "llama8b_32k",
-               "kv_layout_kernel<pack>": 268459785, "kv_layout_kernel<unpack>": 268459928,
-               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135512931 + 1147704}
+PMC_TRAFFIC = {"sha": "afd405b77157f19e", "workload": "llama8b_32k",
+               "kv_layout_kernel<pack>": 268459024, "kv_layout_kernel<unpack>": 268459907,
+               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135498150 + 1151795}
 
 
 def kernel_sources_hash() -> str:
