@@ -214,10 +214,29 @@ SrcDesc make_src(const kv_plan *p, const kv_view_t *v, int layer)
     return s;
 }
 
-// Launch shape, settable for measurement sweeps (defaults are the measured best on MI355X).
-int g_tile_bytes = 0;          // extent bytes one workgroup moves; 0 = 64 KiB (strided source) / 32 KiB (paged)
-int g_run_bytes = 16 * 1024;   // consecutive source bytes per head row and tile to aim for (wide rows)
-int g_unroll = 0;              // token rows in flight per thread: 2, 4 or 8; 0 = 4 (strided source) / 8 (paged)
+// Launch shape.  rx_cap: most lanes (log2) along an extent row; unroll: token rows in flight per thread (2, 4
+// or 8); tile_bytes: extent bytes one workgroup moves; run_bytes: consecutive source bytes per head row a tile
+// should reach when the row is cut into chunks.
+struct Shape {
+    int rx_cap, unroll, tile_bytes, run_bytes;
+};
+
+// Measured best on MI355X (sweeps over rx_cap 4-8, unroll 2/4/8, tiles 16-512 KiB, runs 0.5-64 KiB at the 2 KiB-row
+// and 32 KiB-row shapes, strided and paged, 8 MiB to 256 MiB tensors).  What the table encodes: writes want long
+// contiguous runs, reads tolerate pieces -- so unpack (which writes the attention-side layout) takes one head
+// row per sweep and many tokens, pack (which writes the extent) keeps more lanes along the extent row; a very
+// wide row is cut into chunks so that a tile does not touch every head's stream for a few hundred bytes;
+// launches too small to give every compute unit several tiles take the finer shape.
+Shape pick_shape(bool pack, bool paged, int rowv, unsigned long long launch_bytes)
+{
+    if (rowv > 256) return Shape{8, 4, 64 * 1024, 16 * 1024};
+    if (paged) return pack ? Shape{8, 8, 32 * 1024, 16 * 1024} : Shape{4, 4, 32 * 1024, 16 * 1024};
+    if (!pack || launch_bytes < (64ull << 20)) return Shape{4, 4, 32 * 1024, 16 * 1024};
+    return Shape{5, 8, 64 * 1024, 32 * 1024};
+}
+
+// Measurement override: fields > 0 (rx_cap >= 0) replace the table's.
+Shape g_force{-1, 0, 0, 0};
 bool g_nt_load = true, g_nt_store = true;
 
 template <bool PACK, bool PAGED, int U>
@@ -235,10 +254,9 @@ void launch_nt(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const
 }
 
 template <bool PACK, bool PAGED>
-void launch_u(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv, int rx_log2,
-              int tpb, int rchunk)
+void launch_u(int U, dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv,
+              int rx_log2, int tpb, int rchunk)
 {
-    const int U = g_unroll ? g_unroll : (PAGED ? 8 : 4);
     if (U == 8) launch_nt<PACK, PAGED, 8>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
     else if (U == 2) launch_nt<PACK, PAGED, 2>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
     else launch_nt<PACK, PAGED, 4>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
@@ -248,22 +266,25 @@ template <bool PACK>
 int launch(const kv_plan *p, const kv_view_t *v, int layer, const Seg *segs, int nseg, void *img, hipStream_t stream)
 {
     const int rowv = (int)(p->row_bytes / 16);
-    int rx_log2 = 0;
-    while ((1 << rx_log2) < rowv && rx_log2 < 8) ++rx_log2;
-    const int TY = kThreads >> rx_log2;
     const bool paged = v->layout == KV_LAYOUT_PAGED;
-    // measured best: 64 KiB tiles with 4 rows in flight for a strided source; 32 KiB tiles with 8 rows in flight
-    // for a paged one (ragged batches balance better over finer tiles; +12-16 %)
-    const int U = g_unroll ? g_unroll : (paged ? 8 : 4);
-    const long long tile_bytes = g_tile_bytes ? g_tile_bytes : (paged ? 32 * 1024 : 64 * 1024);
-    // Tile = tpb token rows x rchunk row positions, about g_tile_bytes of extent.  A row wider than one sweep of
-    // the workgroup (many heads x batch) is cut into chunks of row positions, and the tile gets more tokens
-    // instead, so that every source head row it touches contributes at least g_run_bytes of consecutive
-    // tokens: fewer, longer runs per source stream (measured +5-10 % at a 32 KiB row; no effect at 2 KiB rows,
-    // which one sweep covers).
+    unsigned long long launch_bytes = 0;
+    for (int i = 0; i < nseg; ++i) launch_bytes += (unsigned long long)segs[i].ntok * p->row_bytes;
+    Shape sh = pick_shape(PACK, paged, rowv, launch_bytes);
+    if (g_force.rx_cap >= 0) sh.rx_cap = g_force.rx_cap;
+    if (g_force.unroll > 0) sh.unroll = g_force.unroll;
+    if (g_force.tile_bytes > 0) sh.tile_bytes = g_force.tile_bytes;
+    if (g_force.run_bytes > 0) sh.run_bytes = g_force.run_bytes;
+    int rx_log2 = 0;
+    while ((1 << rx_log2) < rowv && rx_log2 < sh.rx_cap) ++rx_log2;
+    const int TY = kThreads >> rx_log2;
+    const int U = sh.unroll;
+    const long long tile_bytes = sh.tile_bytes;
+    // Tile = tpb token rows x rchunk row positions, about tile_bytes of extent.  A row wider than one sweep of
+    // the workgroup is cut into chunks of row positions, and the tile gets more tokens instead, so that every
+    // source head row it touches contributes at least run_bytes of consecutive tokens.
     const long long head_row_bytes = (long long)p->D * 2;
     long long want_tok = tile_bytes / (long long)p->row_bytes;
-    if (rowv > (1 << rx_log2)) want_tok = std::max<long long>(want_tok, g_run_bytes / head_row_bytes);
+    if (rowv > (1 << rx_log2)) want_tok = std::max<long long>(want_tok, sh.run_bytes / head_row_bytes);
     int tpb = (int)std::max<long long>(1, want_tok);
     tpb = (tpb + TY * U - 1) / (TY * U) * (TY * U);
     const int RXv = 1 << rx_log2;
@@ -282,8 +303,8 @@ int launch(const kv_plan *p, const kv_view_t *v, int layer, const Seg *segs, int
             max_tok = std::max(max_tok, segs[g0 + i].ntok);
         }
         dim3 grid((unsigned)std::max(1, (max_tok + tpb - 1) / tpb), (unsigned)n, n_rchunks);
-        if (paged) launch_u<PACK, true>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
-        else launch_u<PACK, false>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
+        if (paged) launch_u<PACK, true>(U, grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
+        else launch_u<PACK, false>(U, grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
     }
@@ -391,11 +412,12 @@ int pack_rows_raw(const kv_plan *p, const kv_view_t *v, int layer, int kind, int
 }
 
 // Measurement hook (not part of the C ABI): launch shape of the pack / unpack kernels.
-void set_layout_tuning(int tile_bytes, int unroll, bool nt_load, bool nt_store, int run_bytes)
+void set_layout_tuning(int tile_bytes, int unroll, bool nt_load, bool nt_store, int run_bytes, int rx_cap)
 {
-    g_tile_bytes = tile_bytes >= 1024 ? tile_bytes : 0;
-    if (run_bytes >= 16) g_run_bytes = run_bytes;
-    g_unroll = (unroll == 2 || unroll == 4 || unroll == 8) ? unroll : 0;
+    g_force.tile_bytes = tile_bytes >= 1024 ? tile_bytes : 0;
+    g_force.unroll = (unroll == 2 || unroll == 4 || unroll == 8) ? unroll : 0;
+    g_force.run_bytes = run_bytes >= 16 ? run_bytes : 0;
+    g_force.rx_cap = (rx_cap >= 0 && rx_cap <= 8) ? rx_cap : -1;
     g_nt_load = nt_load;
     g_nt_store = nt_store;
 }
