@@ -201,11 +201,11 @@ def main():
         table_dev = table.cuda()
         k = [W.paged_layer(cfg, l, 0, n_pool, "cuda") for l in range(L)]
         v = [W.paged_layer(cfg, l, 1, n_pool, "cuda") for l in range(L)]
-        mk = lambda kk, vv: kv.paged_view(kk, vv, table_dev, lens, lens_dev)
+        mk = lambda kk, vv, ln=lens, ld=lens_dev: kv.paged_view(kk, vv, table_dev, ln, ld)
     else:
         k = [W.bhsd_layer(cfg, l, 0, "cuda") for l in range(L)]
         v = [W.bhsd_layer(cfg, l, 1, "cuda") for l in range(L)]
-        mk = lambda kk, vv: kv.bhsd_view(kk, vv, lens, lens_dev)
+        mk = lambda kk, vv, ln=lens, ld=lens_dev: kv.bhsd_view(kk, vv, ln, ld)
     src_view = mk(k, v)
     k2 = [torch.zeros_like(t) for t in k]
     v2 = [torch.zeros_like(t) for t in v]
@@ -351,6 +351,23 @@ def main():
         res["overlap"] = {"serial_s": round(t_serial, 5), "pipeline_s": round(t_pipe, 5), "link_s": round(t_link, 5),
                           "fraction": round((t_serial - t_pipe) / (t_serial - t_link), 3) if t_serial > t_link else None}
         res["decode_attn_us_per_layer_in_pipeline"] = round(attn_us, 2)
+
+        # the decode step's other two forms (outside the timed region): reload with attention straight from the
+        # staged extent images (no unpack), and the append of one new token row to every tensor
+        if not args.attn_from_extent and args.span_chunks == 0:
+            fe = kv.kv_pipeline_run(plan, kv.KV_DIR_RELOAD_ATTN, 0, L, dst_view, region, arena, depth=cfg.depth,
+                                    q_layers=qs, out_layers=outs, host_workers=args.host_workers, attn_from_extent=True)
+            res["reload_attn_from_extent_GBps"] = round(payload / fe.wall_s / 1e9, 2)
+        if min(lens) >= 2:
+            short = [n - 1 for n in lens]   # store all but the last token, then append it
+            short_dev = torch.tensor(short, dtype=torch.int32, device="cuda")
+            kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, mk(k, v, short, short_dev), region, arena, depth=cfg.depth,
+                               host_workers=args.host_workers)
+            t0 = time.perf_counter()
+            ap_st = kv.kv_append_tokens(plan, 0, L, src_view, region, arena)
+            ap_s = time.perf_counter() - t0
+            res["decode_append"] = {"us_all_layers": round(ap_s * 1e6, 1), "write_cmds": int(ap_st.n_cmds),
+                                    "rmw_sector_reads": int(ap_st.n_rmw_reads), "sectors_written": int(ap_st.blocks_written)}
         del region, arena
 
     if args.leg in ("both", "kernels"):
