@@ -361,11 +361,13 @@ def main():
         if min(lens) >= 2:
             short = [n - 1 for n in lens]   # store all but the last token, then append it
             short_dev = torch.tensor(short, dtype=torch.int32, device="cuda")
-            kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, mk(k, v, short, short_dev), region, arena, depth=cfg.depth,
-                               host_workers=args.host_workers)
-            t0 = time.perf_counter()
-            ap_st = kv.kv_append_tokens(plan, 0, L, src_view, region, arena)
-            ap_s = time.perf_counter() - t0
+            short_view = mk(k, v, short, short_dev)
+            for timed in (False, True):      # the first round creates the library's append buffers
+                kv.kv_pipeline_run(plan, kv.KV_DIR_OFFLOAD, 0, L, short_view, region, arena, depth=cfg.depth,
+                                   host_workers=args.host_workers)
+                t0 = time.perf_counter()
+                ap_st = kv.kv_append_tokens(plan, 0, L, src_view, region, arena)
+                ap_s = time.perf_counter() - t0
             res["decode_append"] = {"us_all_layers": round(ap_s * 1e6, 1), "write_cmds": int(ap_st.n_cmds),
                                     "rmw_sector_reads": int(ap_st.n_rmw_reads), "sectors_written": int(ap_st.blocks_written)}
         del region, arena

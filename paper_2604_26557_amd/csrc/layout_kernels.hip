@@ -25,7 +25,6 @@ constexpr int kTblStage = 64;  // block-table entries one workgroup can stage in
 
 // Attention-side addressing, in 16-byte vectors.
 struct SrcDesc {
-    u32x4 *base[2];        // K and V buffers of the layer
     long long sb, sh, ss;  // strided layout: vectors per batch / head / token step
     const int *table;      // paged layout
     int max_blocks, bt, bt_shift, n_pool;
@@ -39,7 +38,7 @@ struct Seg {
     unsigned int pad_vecs;       // zero vectors to write (pack only)
     int b;                       // sequence, or -1: the batch index is part of the row position
     int tok0, ntok;
-    int which;                   // 0: the layer's K buffer, 1: its V buffer
+    u32x4 *base;                 // the attention-side buffer this run belongs to (K or V of some layer)
 };
 
 struct SegTable {
@@ -64,7 +63,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
 {
     const Seg sg = segs.seg[blockIdx.y];
     const int tid = threadIdx.x;
-    u32x4 *const base = s.base[sg.which];
+    u32x4 *const base = sg.base;
 
     if (PACK && sg.pad_vecs && blockIdx.z == 0) {
         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -195,11 +194,14 @@ int check_rows(const kv_plan *p, const kv_view_t *v, int b, int tok0, int ntok)
     return KV_OK;
 }
 
-SrcDesc make_src(const kv_plan *p, const kv_view_t *v, int layer)
+u32x4 *tensor_base(const kv_view_t *v, int layer, int which)
+{
+    return (u32x4 *)(which == 0 ? v->k_layers[layer] : v->v_layers[layer]);
+}
+
+SrcDesc make_src(const kv_plan *p, const kv_view_t *v)
 {
     SrcDesc s{};
-    s.base[0] = (u32x4 *)v->k_layers[layer];
-    s.base[1] = (u32x4 *)v->v_layers[layer];
     s.H = p->H;
     s.dvec = p->D / 8;
     if (v->layout == KV_LAYOUT_BHSD) {
@@ -263,7 +265,7 @@ void launch_u(int U, dim3 grid, hipStream_t stream, const SrcDesc &s, void *img,
 }
 
 template <bool PACK>
-int launch(const kv_plan *p, const kv_view_t *v, int layer, const Seg *segs, int nseg, void *img, hipStream_t stream)
+int launch(const kv_plan *p, const kv_view_t *v, const Seg *segs, int nseg, void *img, hipStream_t stream)
 {
     const int rowv = (int)(p->row_bytes / 16);
     const bool paged = v->layout == KV_LAYOUT_PAGED;
@@ -292,7 +294,7 @@ int launch(const kv_plan *p, const kv_view_t *v, int layer, const Seg *segs, int
     chunk = (chunk + RXv - 1) / RXv * RXv;
     const int rchunk = (int)std::min<long long>(chunk, (rowv + RXv - 1) / RXv * RXv);
     const unsigned n_rchunks = (unsigned)((rowv + rchunk - 1) / rchunk);
-    const SrcDesc s = make_src(p, v, layer);
+    const SrcDesc s = make_src(p, v);
 
     for (int g0 = 0; g0 < nseg; g0 += kMaxSegs) {
         const int n = std::min(kMaxSegs, nseg - g0);
@@ -341,7 +343,7 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
             for (int w = first; w <= last; ++w) {
                 Seg s{};
                 s.img_off = (uint64_t)(w - first) * image / 16;
-                s.b = -1; s.tok0 = 0; s.ntok = len; s.which = w;
+                s.b = -1; s.tok0 = 0; s.ntok = len; s.base = tensor_base(v, layer, w);
                 s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
                 s.pad_vecs = (unsigned)((image - (uint64_t)len * p->row_bytes) / 16);
                 segs.push_back(s);
@@ -356,7 +358,7 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
                     const uint64_t sub_bytes = kvb::round_up((uint64_t)p->cap[b] * p->row_bytes, sec);
                     Seg s{};
                     s.img_off = ((uint64_t)(w - first) * image + p->seq_base[b] * sec) / 16;
-                    s.b = b; s.tok0 = 0; s.ntok = len; s.which = w;
+                    s.b = b; s.tok0 = 0; s.ntok = len; s.base = tensor_base(v, layer, w);
                     s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
                     s.pad_vecs = (unsigned)((sub_bytes - (uint64_t)len * p->row_bytes) / 16);
                     if (len > 0 || s.pad_vecs > 0) segs.push_back(s);
@@ -375,7 +377,7 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
         for (int w = first; w <= last; ++w) {
             Seg s{};
             s.img_off = (uint64_t)(w - first) * r.req_bytes / 16;
-            s.b = b; s.tok0 = tok0; s.ntok = ntok; s.which = w;
+            s.b = b; s.tok0 = tok0; s.ntok = ntok; s.base = tensor_base(v, layer, w);
             s.pad_off = s.img_off + r.payload / 16;
             s.pad_vecs = (unsigned)((r.req_bytes - r.payload) / 16);
             segs.push_back(s);
@@ -384,31 +386,44 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
     if (!PACK)
         for (Seg &s : segs) s.pad_vecs = 0;
     if (segs.empty()) return KV_OK;
-    return launch<PACK>(p, v, layer, segs.data(), (int)segs.size(), img, stream);
+    return launch<PACK>(p, v, segs.data(), (int)segs.size(), img, stream);
 }
 
 }  // namespace
 
 namespace kvb {
-// Token rows [tok0, tok0+ntok) of sequence b (every sequence's in token-major mode: b = -1) of tensor
-// (layer, kind) in extent order at dst, with no sector alignment rule and no padding.  Used by the
-// decode append, whose single rows may start and end inside a sector.
-int pack_rows_raw(const kv_plan *p, const kv_view_t *v, int layer, int kind, int b, int tok0, int ntok, void *dst,
-                  size_t dst_bytes, hipStream_t stream)
+// The newest token row (row len_b - 1, len_b = v->seq_lens_host[b]) of every tensor of layers
+// [layer_begin, layer_end) and every sequence, in extent order, packed back to back at dst in the order
+// (layer, K then V, sequence) -- one row of all sequences per tensor in token-major mode.  No sector
+// alignment rule and no padding: the decode append merges the rows into their sectors on the host.
+// All tensors share launches (one run per row, up to 32 runs per launch).
+int pack_last_rows(const kv_plan *p, const kv_view_t *v, int layer_begin, int layer_end, void *dst, size_t dst_bytes,
+                   hipStream_t stream)
 {
     if (!p || !dst || ((uintptr_t)dst & 15)) return KV_EINVAL;
-    if (kind != KV_K && kind != KV_V) return KV_EINVAL;
-    int rc = check_view(p, v, layer);
-    if (rc != KV_OK) return rc;
-    if (tok0 < 0 || ntok <= 0) return KV_EINVAL;
-    if (p->mode == KV_TOKEN_MAJOR ? b != -1 : (b < 0 || b >= p->B)) return KV_ERANGE;
-    if ((uint64_t)tok0 + (uint64_t)ntok > (uint64_t)p->cap[b < 0 ? 0 : b]) return KV_ERANGE;
-    if (dst_bytes < (uint64_t)ntok * p->row_bytes) return KV_ENOSPC;
-    rc = check_rows(p, v, b, tok0, ntok);
-    if (rc != KV_OK) return rc;
-    Seg s{};
-    s.img_off = 0; s.b = b; s.tok0 = tok0; s.ntok = ntok; s.which = kind;
-    return launch<true>(p, v, layer, &s, 1, dst, stream);
+    if (layer_begin < 0 || layer_end > p->L || layer_begin >= layer_end) return KV_ERANGE;
+    const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
+    const uint64_t n_rows = (uint64_t)(layer_end - layer_begin) * 2 * (uint64_t)nseq;
+    if (dst_bytes < n_rows * p->row_bytes) return KV_ENOSPC;
+    std::vector<Seg> segs;
+    segs.reserve((size_t)n_rows);
+    for (int l = layer_begin; l < layer_end; ++l) {
+        int rc = check_view(p, v, l);
+        if (rc != KV_OK) return rc;
+        for (int kind = 0; kind < 2; ++kind)
+            for (int i = 0; i < nseq; ++i) {
+                const int b = p->mode == KV_TOKEN_MAJOR ? -1 : i;
+                const int len = v->seq_lens_host[i];
+                if (len < 1 || len > p->cap[i]) return KV_ERANGE;
+                rc = check_rows(p, v, b, len - 1, 1);
+                if (rc != KV_OK) return rc;
+                Seg s{};
+                s.img_off = (uint64_t)segs.size() * (p->row_bytes / 16);
+                s.b = b; s.tok0 = len - 1; s.ntok = 1; s.base = tensor_base(v, l, kind);
+                segs.push_back(s);
+            }
+    }
+    return launch<true>(p, v, segs.data(), (int)segs.size(), dst, stream);
 }
 
 // Measurement hook (not part of the C ABI): launch shape of the pack / unpack kernels.

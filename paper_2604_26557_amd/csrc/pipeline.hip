@@ -837,15 +837,8 @@ extern "C" int kv_append_tokens(kv_plan_t *p, int layer_begin, int layer_end, co
     }
 
     // GPU side: the new row of every tensor (and sequence) in extent order, then one transfer
-    size_t idx = 0;
-    for (int l = layer_begin; l < layer_end; ++l)
-        for (int kind = 0; kind < 2; ++kind)
-            for (int b = 0; b < nseq; ++b, ++idx) {
-                const int len = view->seq_lens_host[b];
-                rc = kvb::pack_rows_raw(p, view, l, kind, p->mode == KV_TOKEN_MAJOR ? -1 : b, len - 1, 1,
-                                        (char *)q->staging + idx * rb, rb, q->s_compute);
-                if (rc != KV_OK) { (void)hipStreamSynchronize(q->s_compute); return rc; }
-            }
+    rc = kvb::pack_last_rows(p, view, layer_begin, layer_end, q->staging, q->staging_bytes, q->s_compute);
+    if (rc != KV_OK) { (void)hipStreamSynchronize(q->s_compute); return rc; }
     KV_HIP(hipMemcpyAsync(q->append_host, q->staging, total, hipMemcpyDeviceToHost, q->s_compute));
     KV_HIP(hipStreamSynchronize(q->s_compute));
 
@@ -853,7 +846,7 @@ extern "C" int kv_append_tokens(kv_plan_t *p, int layer_begin, int layer_end, co
     // sectors, so a row that starts inside a sector is merged with that sector's earlier bytes
     // (read-modify-write; the sector image is kept for the next append) and the rest is zeros.
     std::vector<char> tmp;
-    idx = 0;
+    size_t idx = 0;
     for (int l = layer_begin; l < layer_end; ++l)
         for (int kind = 0; kind < 2; ++kind)
             for (int b = 0; b < nseq; ++b, ++idx) {

@@ -59,7 +59,7 @@ int range_cmds(const kv_plan *p, int layer, int kind, int seq, int tok0, int nto
 void set_hip_error(int e);
 
 // layout_kernels.hip
-int pack_rows_raw(const kv_plan *p, const kv_view_t *v, int layer, int kind, int b, int tok0, int ntok, void *dst,
-                  size_t dst_bytes, hipStream_t stream);
+int pack_last_rows(const kv_plan *p, const kv_view_t *v, int layer_begin, int layer_end, void *dst, size_t dst_bytes,
+                   hipStream_t stream);
 
 }  // namespace kvb
