@@ -168,6 +168,48 @@ def test_range_cmds_paper_devices(paper_sizes):
         assert [c.slba for c in cmds] == [2048 + i * n_max for i in range(n_cmds)]
 
 
+def test_random_plans_match_oracle():
+    """Seeded random shapes, sector sizes, extent modes, start LBAs and budgets: every entry of the map, the
+    residency split, the sub-extent bases and the whole-extent commands against the checker."""
+    rng = np.random.default_rng(77)
+    n_checked = 0
+    for _ in range(150):
+        L, H = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        G, D = int(rng.choice([1, 2, 4, 8])), int(rng.choice([64, 128, 256]))
+        B, sec = int(rng.integers(1, 6)), int(rng.choice([512, 4096]))
+        per_seq = bool(rng.integers(0, 2))
+        lens = [int(x) for x in rng.integers(1, 700, size=B)] if per_seq else [int(rng.integers(1, 700))] * B
+        row = (H if per_seq else B * H) * D * 2
+        unit = sec // int(np.gcd(sec, row))
+        C = unit * int(rng.integers(1, 9))
+        lba0 = int(rng.integers(0, 5000))
+        nb = o.tensor_blocks(per_seq, lens, H, D, 2, sec)[0]
+        X = int(rng.integers(0, 2 * (L + 1))) * nb * sec + int(rng.integers(0, sec))
+        p = kv.kv_layout_plan(L, H, H * G, D, lens, kv.KV_F16, sec, C, kv.KV_PER_SEQ if per_seq else kv.KV_TOKEN_MAJOR,
+                              lba0, kv.KV_UNBOUNDED, X, kv.KV_UNBOUNDED)
+        ref = o.layout_plan(L, H, H * G, D, lens, 2, sec, per_seq, X, lba0)
+        info = p.info
+        assert info.n_pagecache_layers == ref.n1 == min(X // (2 * nb * sec), L)      # Alg. 1
+        assert info.tensor_blocks == nb and info.row_bytes == row
+        assert info.pageable_bytes_needed == ref.pageable_bytes
+        for n in range(2 * L):
+            e = kv.kv_plan_tensor(p, n // 2, n % 2)
+            assert (e.path, e.lba_start, e.n_blocks, e.file_off) == \
+                (int(ref.path[n]), int(ref.lba_start[n]), int(ref.n_blocks[n]), int(ref.file_off[n]))
+        nseq = B if per_seq else 1
+        for b in range(nseq):
+            assert kv.kv_plan_seq_base(p, b) == int(ref.seq_base[b])
+            n = int(rng.integers(0, 2 * L))
+            rc, slba, req = o.token_range(ref, n, b, 0, lens[b])
+            assert rc == o.OK
+            want = o.chunk_cmds(slba, req, C * row, sec)
+            got = kv.kv_plan_chunk_cmds(p, n // 2, n % 2, b)
+            assert [(c.slba, c.nlb, c.buf_off) for c in got] == want
+            n_checked += len(got)
+        p.close()
+    assert n_checked > 300
+
+
 def test_pagecache_path_addresses_are_arena_sectors():
     cfg = W.CONFIGS[2]
     p, ref, lens = _plans(cfg)
