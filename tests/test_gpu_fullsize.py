@@ -90,3 +90,57 @@ def test_full_size_offload_reload_attention(idx):
         assert err <= ATTN_ATOL and err <= ATTN_REL_OF_MAX * scale, (layer, err, scale)
     for l in range(L):
         assert torch.isfinite(outs[l]).all()
+
+
+def test_tensor_larger_than_4_gib():
+    """Maximum sizes: one K tensor of 4.58 GiB (byte offsets beyond 2^32, element offsets of the last sequence
+    beyond 2^31).  Whole-tensor pack against the checker byte for byte, unpack back bit for bit, and decode
+    attention of a long last sequence against the fp64 checker."""
+    torch.cuda.set_device(0)
+    H, Hq, D, B, S = 8, 32, 128, 8, 300000
+    print(f"large-tensor case H={H} D={D} B={B} S={S}", flush=True)
+    cfg = W.KVConfig("large_tensor", 4242, 1, H, Hq, D, B, W.F16, 4096, 1024, 3, W.TOKEN_MAJOR, W.BHSD, S)
+    lens = [S] * B
+    plan = kv.kv_layout_plan(1, H, Hq, D, lens, kv.KV_F16, 4096, 1024, kv.KV_TOKEN_MAJOR, 0, kv.KV_UNBOUNDED, 0,
+                             kv.KV_UNBOUNDED)
+    ref = o.layout_plan(1, H, Hq, D, lens, 2, 4096, False, 0, 0)
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    K = torch.randn((B, H, S, D), dtype=torch.float16, device="cuda", generator=g)
+    V = torch.randn((B, H, S, D), dtype=torch.float16, device="cuda", generator=g)
+    nbytes = int(plan.info.tensor_blocks) * 4096
+    assert nbytes == B * H * S * D * 2 > (1 << 32)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    view = kv.bhsd_view([K], [V], lens, lens_dev)
+
+    img = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    kv.kv_offload_pack(plan, 0, kv.KV_K, view, kv.KV_SEQ_ALL, 0, 0, img)
+    torch.cuda.synchronize()
+    K_cpu = K.cpu()
+    want = np.full(nbytes, 0xEE, dtype=np.uint8)
+    o.pack(o.bhsd_source(K_cpu.shape), o.u16(K_cpu), False, lens, ref.seq_base, ref.n_blocks_tensor, 4096, want)
+    got = img.cpu().numpy()
+    assert np.array_equal(got, want)
+    del got, want
+
+    k_new = torch.full(K.shape, 0x7E7E, dtype=torch.int16, device="cuda").view(torch.float16)
+    kv.kv_reload_unpack(plan, 0, kv.KV_K, img, kv.bhsd_view([k_new], [V], lens, lens_dev), kv.KV_SEQ_ALL, 0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(k_new.view(torch.int16), K.view(torch.int16))
+    del k_new, img
+
+    # the last sequence starts 7/8 of the way into the buffers: element offsets beyond 2^31
+    lens2 = [1] * (B - 1) + [50000]
+    view2 = kv.bhsd_view([K], [V], lens2, torch.tensor(lens2, dtype=torch.int32, device="cuda"))
+    q = torch.randn((B, Hq, D), dtype=torch.float16, device="cuda", generator=g)
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(kv.kv_decode_attn_workspace(plan, 0, max(lens2)), dtype=torch.uint8, device="cuda")
+    kv.kv_decode_attn(plan, view2, 0, q, out, kv.KV_OUT_F32, 0, ws)
+    torch.cuda.synchronize()
+    V_cpu = V.cpu()
+    ref_out = o.attention(o.bhsd_source(K_cpu.shape), o.u16(K_cpu), o.u16(V_cpu), o.u16(q.cpu()), False, lens2, Hq)
+    err = np.abs(out.double().cpu().numpy() - ref_out).max()
+    scale = np.abs(ref_out[-1]).max()
+    print(f"  attention max abs err {err:.3e}, reference max of the long sequence {scale:.3e}", flush=True)
+    assert err <= ATTN_ATOL and np.abs(out[-1].double().cpu().numpy() - ref_out[-1]).max() <= ATTN_REL_OF_MAX * scale
+    # a single-token sequence attends to its only token: the output is that V row
+    assert torch.equal(out[0, 0], V[0, 0, 0].float())
