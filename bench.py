@@ -305,6 +305,7 @@ def main():
         link = measure_link(torch, min(payload, 2 << 30))
         off_gbps = payload / off_s / 1e9
         rel_gbps = payload / rel_s / 1e9
+        res["lba_seq_breaks"] = {"offload": int(stats[-1][0].lba_seq_breaks), "reload": int(stats[-1][1].lba_seq_breaks)}
         res["offload_GBps"] = round(off_gbps, 2)
         res["reload_attn_GBps"] = round(rel_gbps, 2)
         res["host_link"] = {"h2d_GBps": round(link["h2d"], 2), "d2h_GBps": round(link["d2h"], 2),

@@ -197,6 +197,10 @@ typedef struct kv_pipe_stats {
     uint32_t kernel_launches[4];
     float kernel_ms[4];       /* summed event-bracketed time per kernel kind (KV_PIPE_TIME_KERNELS); the
                                  attention pair is bracketed together and reported under ATTN_PARTIAL */
+    uint32_t lba_seq_breaks;  /* direct-path commands, in issue order, that do not start at the LBA where the
+                                 previous one ended (Sec. IV-B "Sequential-LBA Placement": 0 for KV_ORDER_CROSS,
+                                 the bind recurrence makes the whole stream one ascending run) */
+    uint32_t reserved;
 } kv_pipe_stats_t;
 
 /* ------------------------------------------------------------------------------------------ */

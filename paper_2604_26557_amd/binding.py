@@ -93,7 +93,8 @@ class kv_pipe_stats_t(C.Structure):
     _fields_ = [("wall_s", C.c_double), ("bytes_direct", C.c_uint64), ("bytes_pagecache", C.c_uint64),
                 ("n_chunks", C.c_uint32), ("n_spans", C.c_uint32), ("max_in_flight", C.c_uint32),
                 ("group_seconds", C.c_double * 2),
-                ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4)]
+                ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4),
+                ("lba_seq_breaks", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class kv_adapt_t(C.Structure):

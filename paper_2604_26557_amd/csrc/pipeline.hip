@@ -280,6 +280,7 @@ struct Schedule {
     std::vector<Chunk> chunks;  // chunk commands, in issue order
     uint64_t slot_bytes = 0;    // largest span image, rounded up to 4 KiB
     long long group_last[2] = {-1, -1};
+    uint32_t lba_seq_breaks = 0;  // direct-path commands that do not continue the previous one's LBA run
 };
 
 // Spans and chunk commands of layers [layer_begin, layer_end): Eq. 7-11 per tensor (and sequence) with C token
@@ -384,6 +385,12 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
     for (size_t i = 0; i < chunks.size(); ++i) {
         chunks[i].first = i == 0 || chunks[i - 1].span != chunks[i].span;
         chunks[i].last = i + 1 == chunks.size() || chunks[i + 1].span != chunks[i].span;
+    }
+    uint64_t prev_end = UINT64_MAX;
+    for (const Chunk &c : chunks) {
+        if (spans[c.span].path != KV_PATH_DIRECT) continue;
+        if (prev_end != UINT64_MAX && c.host_off != prev_end) out->lba_seq_breaks++;
+        prev_end = c.host_off + c.bytes;
     }
     uint64_t slot_bytes = 0;
     for (const Span &s : spans) slot_bytes = std::max(slot_bytes, s.bytes);
@@ -786,6 +793,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         stats->group_seconds[0] = group_t0[0] >= 0 ? group_t1[0] - group_t0[0] : 0.0;
         stats->group_seconds[1] = group_t0[1] >= 0 ? group_t1[1] - group_t0[1] : 0.0;
         stats->max_in_flight = max_in_flight;
+        stats->lba_seq_breaks = sched.lba_seq_breaks;
         if (time_kernels && err == KV_OK) {
             for (size_t i = 0; i < timing_kind.size(); ++i) {
                 float ms = 0.f;

@@ -294,6 +294,7 @@ def test_pipeline_offload_reload(case, span_chunks, depth, copy_streams, d2h, h2
     assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
     assert st.max_in_flight <= depth and st.n_chunks > 0
     assert st.bytes_direct == r.direct_blocks * r.lba_size and st.bytes_pagecache == r.pageable_bytes
+    assert st.lba_seq_breaks == 0        # K then V, layers ascending: one ascending LBA run (Sec. IV-B placement)
 
     k_new, v_new = case.blank_like_source()
     view = case.make_view(k_new, v_new)
@@ -374,6 +375,11 @@ def test_pipeline_overlap_orders(case, span_chunks, order_pc, order_direct):
     _attn_check(outs[0], case.expected_attention(0, qd[0].cpu()))
     assert (st.group_seconds[0] > 0) == (r.n1 > 0) and (st.group_seconds[1] > 0) == (r.n1 < r.L)
     assert st.max_in_flight <= cfg.depth
+    # alternating K and V commands are two interleaved ascending streams: the single run is broken
+    if order_direct == kv.KV_ORDER_INTRA and r.n1 < r.L:
+        assert st.lba_seq_breaks > 0
+    else:
+        assert st.lba_seq_breaks == 0
 
 
 def test_adaptive_strategy_over_decode_iterations(case):
