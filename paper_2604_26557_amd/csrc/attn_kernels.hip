@@ -48,7 +48,8 @@ struct AttnParams {
     const long long *seq_off;  // strided layout, optional: element offset of each sequence (replaces b*sb)
     const int *table;      // paged layout
     int max_blocks, bt, bt_shift, n_pool;
-    int H, Hq, G;
+    int H, Hq, G, B;
+    int compact;           // 1: blockIdx.x counts only the splits that hold tokens, sequence after sequence
     int n_splits, split_tokens;
     int max_len;           // host-checked bound on every sequence length
     float scale_log2e;     // log2(e) / sqrt(D)
@@ -121,9 +122,27 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
     constexpr int AE = 8 * NV;               // accumulator elements per head per lane
     constexpr int TI = tiles_per_iter(D);    // tiles whose loads are issued together (16 KiB in flight per wavefront)
 
-    const int split = blockIdx.x, hq0 = blockIdx.y * GT, b = blockIdx.z;
-    const int h = hq0 / p.G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int split = blockIdx.x, b = blockIdx.z;
+    if (p.compact) {
+        // Ragged batch (B <= 64): no workgroup is launched for a split without tokens.  Lane s holds the split
+        // count of sequence s; an inclusive scan over the wavefront and a ballot find the sequence that owns
+        // work item blockIdx.x (every wavefront does the same).
+        int nb = 0;
+        if (lane < p.B) nb = (min(p.seq_lens[lane], p.max_len) + p.split_tokens - 1) / p.split_tokens;
+        int incl = nb;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const unsigned long long owners = __ballot((int)blockIdx.x < incl);
+        if (owners == 0) return;  // not reached: the grid has exactly the sum of the split counts
+        b = __ffsll((long long)owners) - 1;
+        split = (int)blockIdx.x - __shfl(incl - nb, b);
+    }
+    const int hq0 = blockIdx.y * GT;
+    const int h = hq0 / p.G;
     const int n = lane & 15;    // MFMA column; also the K row this lane loads
     const int tg = lane >> 4;   // row group: owns tokens 4tg..4tg+3 of a tile; also the D sub-slice of the operands
     const int g_own = n % GT;
@@ -353,13 +372,17 @@ constexpr int kMaxSplits = 1024;
 
 __global__ void __launch_bounds__(kCombineThreads)
 kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-                       void *__restrict__ out, int Hq, int D, int n_splits, int out_mode)
+                       void *__restrict__ out, int Hq, int D, int n_splits_alloc, int out_mode,
+                       const int *__restrict__ seq_lens, int len_uniform, int max_len, int split_tokens)
 {
     __shared__ float w[kMaxSplits];
     __shared__ float colsum[kCombineThreads / 64][kCombineCols];
     const int hq = blockIdx.x, b = blockIdx.y, d = blockIdx.z * kCombineCols + (threadIdx.x & (kCombineCols - 1));
     const int tid = threadIdx.x, lane = tid & 63, grp = tid / kCombineCols;
-    const long long o = ((long long)b * Hq + hq) * n_splits;
+    const long long o = ((long long)b * Hq + hq) * n_splits_alloc;
+    // only the splits that hold tokens of this sequence were written (and matter)
+    const int len = len_uniform >= 0 ? len_uniform : min(seq_lens[b], max_len);
+    const int n_splits = min(n_splits_alloc, (len + split_tokens - 1) / split_tokens);
 
     float pre[kCombinePrefetch];
 #pragma unroll
@@ -560,7 +583,7 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
         if (kv->seq_lens_host[b] != max_len) a.len_uniform = -1;
     a.part_acc = (float *)workspace;
     a.part_ml = a.part_acc + (size_t)p->B * p->Hq * ns * p->D;
-    a.H = p->H; a.Hq = p->Hq; a.G = G;
+    a.H = p->H; a.Hq = p->Hq; a.G = G; a.B = p->B;
     a.n_splits = ns;
     a.max_len = max_len;
     a.split_tokens = split_tokens_for(p, ns, max_len);
@@ -568,17 +591,26 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
 
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf16 = p->dtype == KV_BF16;
+    // A ragged batch of up to 64 sequences launches workgroups only for the splits that hold tokens (placed
+    // over the compute units evenly); otherwise the grid is (split, query-head group, sequence).
+    long long n_items = 0;
+    for (int b = 0; b < p->B; ++b) n_items += (std::min(kv->seq_lens_host[b], max_len) + a.split_tokens - 1) / a.split_tokens;
+    a.compact = a.len_uniform < 0 && p->B <= 64;
     dim3 grid((unsigned)ns, (unsigned)(p->Hq / gt), (unsigned)p->B);
-    if (p->D == 64) launch_partial_gt<64>(gt, bf16, paged, grid, st, a);
-    else if (p->D == 128) launch_partial_gt<128>(gt, bf16, paged, grid, st, a);
-    else launch_partial_gt<256>(gt, bf16, paged, grid, st, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
+    if (a.compact) grid = dim3((unsigned)n_items, (unsigned)(p->Hq / gt), 1u);
+    if (n_items > 0) {
+        if (p->D == 64) launch_partial_gt<64>(gt, bf16, paged, grid, st, a);
+        else if (p->D == 128) launch_partial_gt<128>(gt, bf16, paged, grid, st, a);
+        else launch_partial_gt<256>(gt, bf16, paged, grid, st, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
+    }
 
     const int out_mode = out_dtype == KV_OUT_F32 ? 0 : (bf16 ? 2 : 1);
     hipLaunchKernelGGL(kv_attn_combine_kernel, dim3((unsigned)p->Hq, (unsigned)p->B, (unsigned)(p->D / kCombineCols)), dim3(kCombineThreads), 0,
-                       st, a.part_acc, a.part_ml, out, p->Hq, p->D, ns, out_mode);
-    e = hipGetLastError();
+                       st, a.part_acc, a.part_ml, out, p->Hq, p->D, ns, out_mode, a.seq_lens, a.len_uniform, max_len,
+                       a.split_tokens);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
     return KV_OK;
 }
