@@ -26,9 +26,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # llama8b_32k workload (profiles/pmc_traffic_llama8b_32k.md), each counter scaled by what it reads for a
 # plain 128 MiB device-to-device copy in the same run.  Valid only for the kernel sources they were taken
 # with: the hash below covers the two kernel files, and a mismatch reports traffic as null.
-PMC_TRAFFIC = {"sha": "6b810a6cf996000e", "workload": "llama8b_32k",
-               "kv_layout_kernel<pack>": 268485391, "kv_layout_kernel<unpack>": 268467314,
-               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135498557 + 1151794}
+PMC_TRAFFIC = {"sha": "1403d4312564946a", "workload": "llama8b_32k",
+               "kv_layout_kernel<pack>": 268486557, "kv_layout_kernel<unpack>": 268466558,
+               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135508390 + 1147703}
 
 
 def kernel_sources_hash() -> str:
