@@ -62,6 +62,24 @@ def measure_link(torch, total_bytes: int, piece: int = 64 << 20):
     return out
 
 
+def host_memcpy_rate(dst_addr: int, src_addr: int, nbytes: int, threads: int) -> float:
+    """GB/s of `threads` host threads copying disjoint pieces (the third hop of the page-cache path)."""
+    import ctypes
+    import threading
+    piece = nbytes // threads
+
+    def work(i):
+        ctypes.memmove(dst_addr + i * piece, src_addr + i * piece, piece)   # releases the GIL
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(threads)]
+    t0 = time.perf_counter()
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    return piece * threads / (time.perf_counter() - t0) / 1e9
+
+
 def cpu_baseline(cfg, W, budget_s: float = 20.0):
     """The CPU checker (one thread, as it stands) on whole layers of the same workload until about
     budget_s seconds of its own work: pack K and V into extent images, unpack them back, one decode
@@ -326,6 +344,19 @@ def main():
                                    "reload_GBps": round(nb / b.wall_s / 1e9, 2),
                                    "offload_frac_of_link": round(nb / a.wall_s / 1e9 / link["d2h"], 3),
                                    "reload_frac_of_link": round(nb / b.wall_s / 1e9 / link["h2d"], 3)}
+        if n1 > 0:
+            # the extra ceiling of the page-cache path: pinned bounce memory <-> pageable arena by the host threads
+            nthr = args.host_workers or 8
+            nb = min(int(info.pageable_bytes_needed), 1 << 30)
+            pin = torch.empty(nb, dtype=torch.uint8, pin_memory=True)
+            pin.zero_()
+            rates = {"from_arena": 0.0, "to_arena": 0.0}
+            for _ in range(3):   # arena -> pinned, then the same bytes back: the arena keeps its contents
+                rates["from_arena"] = max(rates["from_arena"], host_memcpy_rate(pin.data_ptr(), arena.ctypes.data, nb, nthr))
+                rates["to_arena"] = max(rates["to_arena"], host_memcpy_rate(arena.ctypes.data, pin.data_ptr(), nb, nthr))
+            rates = {k_: round(v_, 1) for k_, v_ in rates.items()}
+            per_path["pagecache"]["host_memcpy_GBps"] = dict(rates, threads=nthr)
+            del pin
         res["per_path"] = per_path
 
         # the two overlap strategies of the adaptive pipeline, one reload each, per path group
