@@ -174,7 +174,7 @@ typedef struct kv_pipe_opts {
                              (K and V in one launch) */
     int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
     uint32_t flags;       /* KV_PIPE_* */
-    int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (2 for the copy kernel,
+    int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (3 for the copy kernel,
                              4 for hipMemcpyAsync);
                              never more than depth */
     int32_t d2h_mode;     /* KV_COPY_* for offload transfers */
