@@ -392,6 +392,10 @@ int kv_adapt_update(kv_adapt_t *a, const kv_pipe_stats_t *stats);
 int kv_last_hip_error(void);       /* hipError_t of the last KV_EHIP on this thread, else 0 */
 const char *kv_strerror(int code); /* static string */
 int kv_abi_version(void);
+/* sizeof of the ABI struct number `which` as this library was compiled (0 kv_plan_desc_t, 1 kv_plan_info_t,
+ * 2 kv_extent_t, 3 kv_cmd_t, 4 kv_view_t, 5 kv_attn_args_t, 6 kv_pipe_opts_t, 7 kv_pipe_stats_t,
+ * 8 kv_append_stats_t, 9 kv_adapt_t; 0 for any other number): lets a binding verify its own layouts. */
+size_t kv_abi_sizeof(int which);
 
 #ifdef __cplusplus
 }

@@ -36,6 +36,7 @@ EXPORTS = [
     "kv_plan_translate", "kv_plan_chunk_cmds", "kv_plan_range_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
     "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
+    "kv_abi_sizeof",
 ]
 
 
@@ -148,8 +149,15 @@ def lib() -> C.CDLL:
         L.kv_adapt_update.argtypes = [C.POINTER(kv_adapt_t), C.POINTER(kv_pipe_stats_t)]
         L.kv_strerror.restype = C.c_char_p
         L.kv_strerror.argtypes = [i]
+        L.kv_abi_sizeof.argtypes = [i]
+        L.kv_abi_sizeof.restype = C.c_size_t
         for name in EXPORTS:
             getattr(L, name)
+        # the ctypes mirrors must have the library's own struct sizes
+        for which, t in enumerate((kv_plan_desc_t, kv_plan_info_t, kv_extent_t, kv_cmd_t, kv_view_t, kv_attn_args_t,
+                                   kv_pipe_opts_t, kv_pipe_stats_t, kv_append_stats_t, kv_adapt_t)):
+            if L.kv_abi_sizeof(which) != C.sizeof(t):
+                raise RuntimeError(f"{t.__name__}: binding has {C.sizeof(t)} bytes, library {L.kv_abi_sizeof(which)}")
         _lib = L
     return _lib
 

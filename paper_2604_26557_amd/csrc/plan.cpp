@@ -352,6 +352,23 @@ extern "C" int kv_adapt_update(kv_adapt_t *a, const kv_pipe_stats_t *st)
     return KV_OK;
 }
 
+extern "C" size_t kv_abi_sizeof(int which)
+{
+    switch (which) {
+    case 0: return sizeof(kv_plan_desc_t);
+    case 1: return sizeof(kv_plan_info_t);
+    case 2: return sizeof(kv_extent_t);
+    case 3: return sizeof(kv_cmd_t);
+    case 4: return sizeof(kv_view_t);
+    case 5: return sizeof(kv_attn_args_t);
+    case 6: return sizeof(kv_pipe_opts_t);
+    case 7: return sizeof(kv_pipe_stats_t);
+    case 8: return sizeof(kv_append_stats_t);
+    case 9: return sizeof(kv_adapt_t);
+    default: return 0;
+    }
+}
+
 extern "C" int kv_last_hip_error(void) { return g_last_hip_error; }
 
 extern "C" const char *kv_strerror(int code)

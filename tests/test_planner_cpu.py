@@ -35,6 +35,7 @@ def test_header_symbols_exported():
     for name in declared:
         assert hasattr(lib, name)
     assert lib.kv_abi_version() == 2
+    assert lib.kv_abi_sizeof(7) == kv.C.sizeof(kv.kv_pipe_stats_t) and lib.kv_abi_sizeof(99) == 0
 
 
 @pytest.mark.parametrize("idx", range(5))
