@@ -200,7 +200,9 @@ def main():
     from paper_2604_26557_amd import workloads as W
     from kvcase import native_plan
 
-    kv.lib()  # fail loudly if the HIP library is missing
+    from paper_2604_26557_amd import build as native_build
+    native_build.build_if_missing()   # a harness may build; the binding itself never does
+    kv.lib()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
     cfg = W.config(args.config)
     lens = W.seq_lens(cfg)

@@ -53,6 +53,12 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_if_missing() -> str:
+    """For harnesses (tests, smoke, bench): build only when no library has been built.  The binding itself
+    never builds and never falls back: it raises when the library is missing."""
+    return LIB if os.path.exists(LIB) else build(verbose=False)
+
+
 if __name__ == "__main__":
     build()
     print(LIB)

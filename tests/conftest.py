@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # load what is built; build only when nothing is
+    from paper_2604_26557_amd import build
+    build.build_if_missing()
+
+
 def golden(name):
     """Parse tests/golden/<name>: 'key = value  # citation' lines into {key: int}."""
     out = {}
