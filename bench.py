@@ -80,7 +80,7 @@ def host_memcpy_rate(dst_addr: int, src_addr: int, nbytes: int, threads: int) ->
     return piece * threads / (time.perf_counter() - t0) / 1e9
 
 
-def cpu_baseline(cfg, W, budget_s: float = 20.0):
+def cpu_baseline(cfg, W, budget_s: float = 20.0, gpu_attn=None):
     """The CPU checker (one thread, as it stands) on whole layers of the same workload until about
     budget_s seconds of its own work: pack K and V into extent images, unpack them back, one decode
     attention.  Only the checker's calls are timed, not the input generation."""
@@ -104,8 +104,11 @@ def cpu_baseline(cfg, W, budget_s: float = 20.0):
             o.unpack(src, back, plan.per_seq, lens, plan.seq_base, plan.lba_size, ext)
             moved += 2 * nbytes  # once out, once back
         t1 = time.perf_counter()
-        o.attention(src, o.u16(K), o.u16(V), o.u16(q), cfg.dtype == W.BF16, lens, cfg.n_q_heads)
+        ref = o.attention(src, o.u16(K), o.u16(V), o.u16(q), cfg.dtype == W.BF16, lens, cfg.n_q_heads)
         t2 = time.perf_counter()
+        if layer == 0 and gpu_attn is not None:   # the same bits through the GPU path, against the checker's output
+            got = gpu_attn(K, V, q)
+            parity = {"layer": 0, "max_abs_err": float(np.abs(got - ref).max()), "reference_max_abs": float(np.abs(ref).max())}
         move_s += t1 - t0
         attn_s += t2 - t1
         layers += 1
@@ -116,7 +119,8 @@ def cpu_baseline(cfg, W, budget_s: float = 20.0):
             "sample": f"{layers} of {cfg.n_layers} layers of the same workload: pack+unpack of K and V and one decode "
                       f"attention per layer, plain C checker, 1 thread, {total:.1f} s",
             "pack_unpack_GBps": round(2 * moved / move_s / 1e9, 3),
-            "decode_attn_us_per_layer": round(attn_s / layers * 1e6, 1)}
+            "decode_attn_us_per_layer": round(attn_s / layers * 1e6, 1),
+            "gpu_attention_vs_checker": parity if gpu_attn is not None else None}
 
 
 def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps: int):
@@ -428,7 +432,16 @@ def main():
 
     if not args.no_cpu_baseline and cfg.layout == W.BHSD:
         log("[bench] timing the CPU checker on a bounded sample ...")
-        res["cpu_baseline"] = cpu_baseline(cfg, W)
+        def gpu_attn(K, V, q):
+            Kd, Vd, qd = K.cuda(), V.cuda(), q.cuda()
+            view = kv.bhsd_view([Kd], [Vd], lens, lens_dev)
+            out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+            ws = torch.empty(kv.kv_decode_attn_workspace(plan, 0, max(lens)), dtype=torch.uint8, device="cuda")
+            kv.kv_decode_attn(plan, view, 0, qd, out, kv.KV_OUT_F32, 0, ws)
+            torch.cuda.synchronize()
+            return out.double().cpu().numpy()
+
+        res["cpu_baseline"] = cpu_baseline(cfg, W, gpu_attn=gpu_attn)
     print(json.dumps(res), flush=True)
 
 
