@@ -26,9 +26,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # llama8b_32k workload (profiles/pmc_traffic_llama8b_32k.md), each counter scaled by what it reads for a
 # plain 128 MiB device-to-device copy in the same run.  Valid only for the kernel sources they were taken
 # with: the hash below covers the two kernel files, and a mismatch reports traffic as null.
-PMC_TRAFFIC = {"sha": "1403d4312564946a", "workload": "llama8b_32k",
-               "kv_layout_kernel<pack>": 268486557, "kv_layout_kernel<unpack>": 268466558,
-               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135508390 + 1147703}
+PMC_TRAFFIC = {"sha": "540b7d6a921b615a", "workload": "llama8b_32k",
+               "kv_layout_kernel<pack>": 268486797, "kv_layout_kernel<unpack>": 268468985,
+               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135508062 + 1147700}
 
 
 def kernel_sources_hash() -> str:

@@ -224,11 +224,12 @@ struct Shape {
 };
 
 // Measured best on MI355X (sweeps over rx_cap 4-8, unroll 2/4/8, tiles 16-512 KiB, runs 0.5-64 KiB at the 2 KiB-row
-// and 32 KiB-row shapes, strided and paged, 8 MiB to 256 MiB tensors).  What the table encodes: writes want long
-// contiguous runs, reads tolerate pieces -- so unpack (which writes the attention-side layout) takes one head
-// row per sweep and many tokens, pack (which writes the extent) keeps more lanes along the extent row; a very
-// wide row is cut into chunks so that a tile does not touch every head's stream for a few hundred bytes;
-// launches too small to give every compute unit several tiles take the finer shape.
+// and 32 KiB-row shapes, strided and paged, 8 MiB to 256 MiB tensors).  What the table encodes: a tile should touch
+// few attention-side head streams, each for a long run of consecutive tokens; on the extent side 256-512 byte
+// pieces are fine, since they fall inside one compact window of the image.  So a narrow row gets 16-32 lanes along
+// the row and 64-128 tokens per tile, a very wide row is cut into chunks so that a tile does not touch every head's
+// stream for a few hundred bytes, and launches too small to give every compute unit several tiles take the finer
+// shape.  The pack / unpack difference in lane count and unroll is empirical.
 Shape pick_shape(bool pack, bool paged, int rowv, unsigned long long launch_bytes)
 {
     if (rowv > 256) return Shape{8, 4, 64 * 1024, 16 * 1024};
