@@ -362,6 +362,16 @@ int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, int32_t n_th
               int64_t *m_star, int64_t *b_pc);
 
 /*
+ * kv_budget_sample -- the three memory figures of Eq. 1 "under system and cgroup limits" (Sec. IV-A "Plan"),
+ * sampled now on this Linux host, in bytes: M_avail = MemAvailable of /proc/meminfo; M_max = the memory limit of
+ * this process's cgroup (cgroup v2 memory.max, else v1 memory.limit_in_bytes), or MemTotal when there is no
+ * limit; M_anon+shmem = anon + shmem of the cgroup's memory.stat (v1: rss + shmem) when it has a limit, else
+ * AnonPages + Shmem of /proc/meminfo.  root = "" or NULL reads the real files; another root directory is
+ * prepended to every path (for tests).  KV_EINVAL if /proc/meminfo cannot be read or lacks a field.
+ */
+int kv_budget_sample(const char *root, int64_t *m_avail, int64_t *m_max, int64_t *m_anon_shmem);
+
+/*
  * kv_plan_trim -- context teardown (Sec. IV-B "Dataset Management--Deallocate"): for every tensor of
  * layers [layer_begin, layer_end) the range <lba_start, n_blocks> of the map M is given back.  In the
  * host-memory model a deallocated block reads back as zeros: the extent bytes in lba_region (direct

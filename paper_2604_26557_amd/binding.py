@@ -36,7 +36,7 @@ EXPORTS = [
     "kv_plan_translate", "kv_plan_chunk_cmds", "kv_plan_range_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
     "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
-    "kv_abi_sizeof",
+    "kv_abi_sizeof", "kv_budget_sample",
 ]
 
 
@@ -142,6 +142,7 @@ def lib() -> C.CDLL:
                                        C.POINTER(kv_append_stats_t)]
         L.kv_budget.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.POINTER(C.c_int64),
                                 C.POINTER(C.c_int64)]
+        L.kv_budget_sample.argtypes = [C.c_char_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.kv_plan_trim.argtypes = [vp, i, i, vp, C.c_size_t, vp, C.c_size_t, C.POINTER(C.c_uint64),
                                    C.POINTER(C.c_uint64)]
         L.kv_adapt_init.argtypes = [C.POINTER(kv_adapt_t)]
@@ -397,6 +398,13 @@ def kv_append_tokens(plan: Plan, layer_begin: int, layer_end: int, view: View, l
     _check(lib().kv_append_tokens(plan.handle, layer_begin, layer_end, view.ref(), rp, rb, pp, pb, C.byref(st)),
            "kv_append_tokens")
     return st
+
+
+def kv_budget_sample(root: str = ""):
+    """(M_avail, M_max, M_anon+shmem) in bytes, sampled now (Eq. 1's inputs)."""
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib().kv_budget_sample(root.encode(), C.byref(a), C.byref(b), C.byref(c)), "kv_budget_sample")
+    return int(a.value), int(b.value), int(c.value)
 
 
 def kv_budget(m_avail: int, m_max: int, m_anon_shmem: int, n_threads: int, m_pin: int):

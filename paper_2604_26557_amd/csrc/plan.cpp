@@ -3,8 +3,12 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <cstdio>
 #include <cstring>
+#include <fstream>
 #include <new>
+#include <sstream>
+#include <string>
 
 namespace kvb {
 
@@ -282,6 +286,81 @@ extern "C" int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, i
     *m_star = std::min(m_avail, limit);
     const int64_t left = *m_star - (int64_t)n_threads * m_pin;  // Eq. 2
     *b_pc = std::max<int64_t>(0, left);
+    return KV_OK;
+}
+
+namespace {
+
+// value of "key" in a file of "key value [unit]" lines (a trailing ':' on the key is ignored); -1 if absent
+int64_t file_field(const std::string &path, const std::string &key)
+{
+    std::ifstream f(path);
+    std::string line;
+    while (std::getline(f, line)) {
+        std::istringstream ss(line);
+        std::string k;
+        long long v;
+        if (!(ss >> k >> v)) continue;
+        if (!k.empty() && k.back() == ':') k.pop_back();
+        if (k == key) return (int64_t)v;
+    }
+    return -1;
+}
+
+// first token of a one-line file: a number, or "max" (-> -2); -1 if the file cannot be read
+int64_t file_number(const std::string &path)
+{
+    std::ifstream f(path);
+    std::string tok;
+    if (!(f >> tok)) return -1;
+    if (tok == "max") return -2;
+    char *end = nullptr;
+    const long long v = std::strtoll(tok.c_str(), &end, 10);
+    return end && *end == 0 ? (int64_t)v : -1;
+}
+
+// this process's cgroup directory: v2 line "0::/path" -> /sys/fs/cgroup/path; v1 line "N:memory:/path" ->
+// /sys/fs/cgroup/memory/path
+void cgroup_dirs(const std::string &root, std::string *v2, std::string *v1)
+{
+    std::ifstream f(root + "/proc/self/cgroup");
+    std::string line;
+    *v2 = root + "/sys/fs/cgroup";
+    *v1 = root + "/sys/fs/cgroup/memory";
+    while (std::getline(f, line)) {
+        const size_t a = line.find(':'), b = a == std::string::npos ? a : line.find(':', a + 1);
+        if (b == std::string::npos) continue;
+        const std::string ctrl = line.substr(a + 1, b - a - 1), path = line.substr(b + 1);
+        if (ctrl.empty()) *v2 = root + "/sys/fs/cgroup" + (path == "/" ? "" : path);
+        else if (("," + ctrl + ",").find(",memory,") != std::string::npos) *v1 = root + "/sys/fs/cgroup/memory" + (path == "/" ? "" : path);
+    }
+}
+
+}  // namespace
+
+extern "C" int kv_budget_sample(const char *root_c, int64_t *m_avail, int64_t *m_max, int64_t *m_anon_shmem)
+{
+    if (!m_avail || !m_max || !m_anon_shmem) return KV_EINVAL;
+    const std::string root = root_c ? root_c : "";
+    const std::string meminfo = root + "/proc/meminfo";
+    const int64_t avail = file_field(meminfo, "MemAvailable"), total = file_field(meminfo, "MemTotal");
+    const int64_t anon = file_field(meminfo, "AnonPages"), shmem = file_field(meminfo, "Shmem");
+    if (avail < 0 || total < 0 || anon < 0 || shmem < 0) return KV_EINVAL;
+    *m_avail = avail * 1024;   // /proc/meminfo counts KiB
+    *m_max = total * 1024;
+    *m_anon_shmem = (anon + shmem) * 1024;
+
+    std::string v2, v1;
+    cgroup_dirs(root, &v2, &v1);
+    int64_t limit = file_number(v2 + "/memory.max");
+    bool is_v2 = true;
+    if (limit == -1) { limit = file_number(v1 + "/memory.limit_in_bytes"); is_v2 = false; }
+    if (limit >= 0 && limit < *m_max) {  // a real limit below the machine's memory
+        *m_max = limit;
+        const std::string stat = (is_v2 ? v2 : v1) + "/memory.stat";
+        const int64_t a = file_field(stat, is_v2 ? "anon" : "rss"), s = file_field(stat, "shmem");
+        if (a >= 0 && s >= 0) *m_anon_shmem = a + s;   // memory.stat counts bytes
+    }
     return KV_OK;
 }
 

@@ -312,3 +312,54 @@ def test_adaptive_selection_matches_oracle():
                 thr[1][orders[1]] = 3.0 / secs[1]
             kv.kv_adapt_update(a, st)
         assert a.iteration == 7
+
+
+def _fake_root(tmp_path, meminfo, cgroup_line=None, files=None):
+    (tmp_path / "proc" / "self").mkdir(parents=True)
+    (tmp_path / "proc" / "meminfo").write_text(meminfo)
+    if cgroup_line is not None:
+        (tmp_path / "proc" / "self" / "cgroup").write_text(cgroup_line + "\n")
+    for rel, text in (files or {}).items():
+        f = tmp_path / rel
+        f.parent.mkdir(parents=True, exist_ok=True)
+        f.write_text(text)
+    return str(tmp_path)
+
+
+MEMINFO = "MemTotal:       16000000 kB\nMemFree:         1000000 kB\nMemAvailable:    9000000 kB\nAnonPages:       2000000 kB\nShmem:            500000 kB\n"
+
+
+def test_budget_sample_system_and_cgroup_limits(tmp_path):
+    """Eq. 1's inputs under system and cgroup limits, from fixture files, then through Eq. 1-2."""
+    KiB = 1024
+    # no cgroup limit: the machine's memory and its anon + shmem
+    root = _fake_root(tmp_path / "a", MEMINFO, "0::/", {"sys/fs/cgroup/memory.max": "max\n"})
+    assert kv.kv_budget_sample(root) == (9000000 * KiB, 16000000 * KiB, 2500000 * KiB)
+    # cgroup v2 limit of 4 GiB in a nested group, its own anon + shmem (bytes)
+    root = _fake_root(tmp_path / "b", MEMINFO, "0::/serve/llm", {
+        "sys/fs/cgroup/serve/llm/memory.max": str(4 << 30) + "\n",
+        "sys/fs/cgroup/serve/llm/memory.stat": "anon 1000000000\nfile 5\nshmem 24000000\n"})
+    got = kv.kv_budget_sample(root)
+    assert got == (9000000 * KiB, 4 << 30, 1024000000)
+    # Eq. 1-2 on the sample: M* = min(M_avail, M_max - M_anon+shmem), B_pc = max(0, M* - N_threads M_pin)
+    m_star, b_pc = kv.kv_budget(*got, 2, 128 << 20)
+    assert (m_star, b_pc) == o.budget(*got, 2, 128 << 20)
+    assert m_star == (4 << 30) - 1024000000 and b_pc == m_star - (256 << 20)
+    # cgroup v1 (memory controller line), rss + shmem
+    root = _fake_root(tmp_path / "c", MEMINFO, "4:cpu,memory:/box", {
+        "sys/fs/cgroup/memory/box/memory.limit_in_bytes": "2147483648\n",
+        "sys/fs/cgroup/memory/box/memory.stat": "cache 1\nrss 300000000\nshmem 1000000\n"})
+    assert kv.kv_budget_sample(root) == (9000000 * KiB, 2147483648, 301000000)
+    # a limit above the machine's memory is no limit
+    root = _fake_root(tmp_path / "d", MEMINFO, "0::/", {"sys/fs/cgroup/memory.max": str(1 << 50) + "\n"})
+    assert kv.kv_budget_sample(root)[1:] == (16000000 * KiB, 2500000 * KiB)
+    # unreadable or incomplete /proc/meminfo
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_budget_sample(str(tmp_path / "nowhere"))
+    assert e.value.code == kv.KV_EINVAL
+    root = _fake_root(tmp_path / "e", "MemTotal: 5 kB\n")
+    with pytest.raises(kv.KVError):
+        kv.kv_budget_sample(root)
+    # the real host: plausible figures
+    a, m, s_ = kv.kv_budget_sample()
+    assert 0 < a <= m * 2 and m > 0 and s_ >= 0
