@@ -272,6 +272,30 @@ def test_decode_attention_16bit_output_and_short_lengths(case):
         assert not out32[1].any()
 
 
+@pytest.mark.parametrize("B", [64, 65, 130])
+@pytest.mark.parametrize("n_splits", [0, 5])
+def test_decode_attention_many_ragged_sequences(B, n_splits):
+    """Ragged batches at and beyond 64 sequences: up to 64 the grid holds only the splits with tokens (the owner
+    search uses one lane per sequence), beyond that the full (split, head group, sequence) grid runs and the
+    combine pass reads each sequence's own split count.  Some sequences are empty."""
+    cfg = W.KVConfig(f"many{B}", 500 + B, 1, 2, 4, 64, B, W.F16, 512, 4, 2, W.PER_SEQ, W.BHSD, 0, len_range=(1, 900))
+    lens = W.seq_lens(cfg)
+    lens[3] = 0
+    lens[B - 1] = 0
+    lens[B // 2] = 900
+    case = Case(cfg, "cuda", gen_device="cpu", lens=lens)
+    view = case.make_view(case.k, case.v, lens)
+    q = W.query(cfg, 0, "cpu")
+    out = torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, n_splits, max(lens)), dtype=torch.uint8, device="cuda")
+    kv.kv_decode_attn(case.plan, view, 0, q.cuda(), out, kv.KV_OUT_F32, n_splits, ws)
+    torch.cuda.synchronize()
+    K, V = case.k_cpu[0], case.v_cpu[0]
+    want = o.attention(case.source(K), o.u16(K), o.u16(V), o.u16(q), False, lens, cfg.n_q_heads)
+    _attn_check(out, want)
+    assert not out[3].any() and not out[B - 1].any()
+
+
 # ------------------------------------------------------------------------------------------ pipeline
 # (span_chunks, depth, copy_streams, d2h_mode, h2d_mode)
 PIPE_VARIANTS = [(0, 3, 0, kv.KV_COPY_AUTO, kv.KV_COPY_AUTO),
