@@ -563,6 +563,31 @@ def test_decode_append(cfg):
     assert e.value.code == kv.KV_ERANGE
 
 
+def test_many_sequences_span_several_launches():
+    """70 ragged per-sequence sub-extents per tensor: the pack / unpack segment table holds 32 runs, so one tensor
+    takes several launches; the append packs 140 rows.  Host bytes, round trip and append against the checker."""
+    B, EXTRA = 70, 1
+    cfg = W.KVConfig("many_segments", 777, 1, 2, 4, 64, B, W.BF16, 512, 4, 3, W.PER_SEQ, W.BHSD, 0, len_range=(1, 300))
+    lens = W.seq_lens(cfg)
+    lens[5] = 0
+    case = Case(cfg, "cuda", gen_device="cpu", lens=lens, cap_extra=EXTRA)
+    r = case.ref
+    FILL = 0x6D
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, 1, case.view, region, arena, depth=3)
+    want_region, _ = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    k_new, v_new = case.blank_like_source()
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, 1, case.make_view(k_new, v_new), region, arena, depth=3)
+    _check_restored(case, k_new, v_new, [0])
+    longer = [n + 1 for n in lens]
+    st = kv.kv_append_tokens(case.plan, 0, 1, case.make_view(case.k, case.v, longer), region, arena)
+    assert st.n_cmds == 2 * B
+    want_region, _ = case.expected_host(fill=FILL, lens=longer)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+
+
 # ------------------------------------------------------------------------------------------ random shapes
 def _random_configs(n, seed):
     rng = np.random.default_rng(seed)
