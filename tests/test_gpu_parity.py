@@ -581,6 +581,12 @@ def test_many_sequences_span_several_launches():
     k_new, v_new = case.blank_like_source()
     kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, 1, case.make_view(k_new, v_new), region, arena, depth=3)
     _check_restored(case, k_new, v_new, [0])
+    # attention straight from the staged image: 70 per-sequence base offsets, ragged lengths (full grid: B > 64)
+    q = W.query(cfg, 0, "cpu")
+    out = [torch.full((B, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")]
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, 1, case.make_view(k_new, v_new), region, arena, depth=3,
+                       q_layers=[q.cuda()], out_layers=out, attn_from_extent=True)
+    _attn_check(out[0], case.expected_attention(0, q))
     longer = [n + 1 for n in lens]
     st = kv.kv_append_tokens(case.plan, 0, 1, case.make_view(case.k, case.v, longer), region, arena)
     assert st.n_cmds == 2 * B
