@@ -519,7 +519,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // flight; with page-cache-path layers the ring is twice as long, so that a bounce slot can wait for its
     // host copy (the memcpy hop is not a device command) without holding back the next transfer.
     const size_t NB = any_pc ? 2 * (size_t)depth : (size_t)depth;
-    int rc = ensure_pipeline(p, n_slots, slot_bytes, (int)NB, chunk_bytes, any_pc, n_workers, ws_bytes, n_timing);
+    // a bounce slot holds the largest page-cache-path command of this schedule (not the nominal chunk size: a
+    // chunk may be larger than every extent, or cut down by the transfer-size limit)
+    uint64_t bounce_slot = 0;
+    for (const Chunk &c : chunks)
+        if (spans[c.span].path == KV_PATH_PAGECACHE) bounce_slot = std::max(bounce_slot, c.bytes);
+    bounce_slot = kvb::round_up(bounce_slot, 4096);
+    int rc = ensure_pipeline(p, n_slots, slot_bytes, (int)NB, bounce_slot, any_pc, n_workers, ws_bytes, n_timing);
     if (rc != KV_OK) return rc;
     kv_pipeline *q = p->pipe;
     if (attn_from_extent && p->mode == KV_PER_SEQ && !q->seq_off_dev) {
@@ -581,7 +587,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     auto host_ptr = [&](const Chunk &ch) -> char * {
         return (spans[ch.span].path == KV_PATH_DIRECT ? (char *)lba_region : (char *)pageable) + ch.host_off;
     };
-    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % NB) * chunk_bytes; };
+    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % NB) * bounce_slot; };
     auto fan_out = [&](size_t c, void *dst, const void *src, size_t bytes, hipEvent_t ev) {
         Entry &e = q->ring[c % NB];
         int pieces = (int)std::min<size_t>((size_t)pieces_max, std::max<size_t>(1, bytes / (256 * 1024)));
