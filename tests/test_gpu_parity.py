@@ -328,6 +328,29 @@ def test_pipeline_offload_reload(case, span_chunks, depth, copy_streams, d2h, h2
     _check_restored(case, k_new, v_new, range(cfg.n_layers))
 
 
+def test_pipeline_serialized_reference_run(case):
+    """The no-overlap reference of the overlap fraction (every stage to completion before the next): same bytes,
+    same reload, same attention, one command in flight."""
+    cfg, r = case.cfg, case.ref
+    FILL = 0x11
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=1, serialize=True)
+    assert st.max_in_flight == 1
+    want_region, want_arena = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    k_new, v_new = case.blank_like_source()
+    qd = [W.query(cfg, l, "cpu").cuda() for l in range(cfg.n_layers)]
+    outs = [torch.zeros((len(case.lens), cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+            for _ in range(cfg.n_layers)]
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD_ATTN, 0, cfg.n_layers, case.make_view(k_new, v_new), region, arena,
+                            depth=1, serialize=True, q_layers=qd, out_layers=outs)
+    assert st.max_in_flight == 1
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+    _attn_check(outs[-1], case.expected_attention(cfg.n_layers - 1, qd[-1].cpu()))
+
+
 @pytest.mark.parametrize("span_chunks", [0, 1])
 def test_pipeline_reload_attention(case, span_chunks):
     cfg, r = case.cfg, case.ref
