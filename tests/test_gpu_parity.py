@@ -526,6 +526,14 @@ def test_pipeline_argument_errors(case):
         return e.value.code
 
     assert code(depth=0) == kv.KV_EINVAL
+    assert code(depth=1025) == kv.KV_EINVAL
+    assert code(chunk_tokens=-1) == kv.KV_EINVAL
+    assert code(copy_streams=5) == kv.KV_EINVAL
+    assert code(d2h_mode=7) == kv.KV_EINVAL and code(h2d_mode=-1) == kv.KV_EINVAL
+    assert code(order_pagecache=3) == kv.KV_EINVAL and code(order_direct=-1) == kv.KV_EINVAL
+    assert code(host_workers=65) == kv.KV_EINVAL
+    assert code(span_chunks=-1) == kv.KV_EINVAL
+    assert code(attn_from_extent=True) == kv.KV_EINVAL                      # only with KV_DIR_RELOAD_ATTN
     assert code(direction=9) == kv.KV_EINVAL
     assert code(layer_end=cfg.n_layers + 1) == kv.KV_ERANGE
     assert code(direction=kv.KV_DIR_RELOAD_ATTN) == kv.KV_EINVAL            # no attention arguments
