@@ -221,6 +221,25 @@ def test_kernel_argument_errors(case):
     assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, kv.KV_SEQ_ALL, 0, 0, dst[8:])) == kv.KV_EINVAL
     if (r.row_bytes % r.lba_size) != 0 and cap > 2:
         assert code(lambda: kv.kv_offload_pack(case.plan, 0, 0, case.view, 0, 1, 1, dst)) == kv.KV_EALIGN
+    assert code(lambda: kv.kv_reload_unpack(case.plan, 0, 0, dst[:4096], case.view, kv.KV_SEQ_ALL, 0, 0)) == kv.KV_ENOSPC
+    assert code(lambda: kv.kv_reload_unpack(case.plan, -1, 0, dst, case.view, kv.KV_SEQ_ALL, 0, 0)) == kv.KV_ERANGE
+
+    # decode attention
+    cfg = case.cfg
+    q = W.query(cfg, 0, "cuda")
+    out = torch.zeros((len(case.lens), cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+    ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, 0, max(case.lens)), dtype=torch.uint8, device="cuda")
+    attn = lambda **kw: kv.kv_decode_attn(**dict(dict(plan=case.plan, kv=case.view, layer=0, q=q, out=out,
+                                                      out_dtype=kv.KV_OUT_F32, n_splits=0, workspace=ws), **kw))
+    attn()
+    torch.cuda.synchronize()
+    assert code(lambda: attn(layer=99)) == kv.KV_ERANGE
+    assert code(lambda: attn(out_dtype=5)) == kv.KV_EINVAL
+    assert code(lambda: attn(n_splits=1025)) == kv.KV_EINVAL
+    assert code(lambda: attn(n_splits=-1)) == kv.KV_EINVAL
+    assert code(lambda: attn(workspace=ws[:64])) == kv.KV_ENOSPC
+    misaligned = torch.zeros(q.numel() * 2 + 16, dtype=torch.uint8, device="cuda")[2:]
+    assert code(lambda: attn(q=misaligned)) == kv.KV_EINVAL
 
 
 # ------------------------------------------------------------------------------------------ attention
