@@ -306,6 +306,20 @@ int kv_decode_attn(const kv_plan_t *plan, const kv_view_t *kv, int layer, const 
  * for whatever split count the library chooses at that length). */
 size_t kv_decode_attn_workspace(const kv_plan_t *plan, int n_splits, int max_len);
 
+/*
+ * kv_decode_attn_static -- kv_decode_attn for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, result and errors,
+ * but no workspace argument.  The split partials live in an array of KV_ATTN_SCRATCH_BYTES that is part of
+ * the library's device image (each GPU the library runs on holds it until the process ends); the call
+ * allocates and frees nothing.  KV_ENOSPC if the partials of this call,
+ * batch * n_q_heads * splits * (head_dim + 2) * 4 bytes, exceed the array (pass a smaller n_splits, or use
+ * kv_decode_attn with a workspace).  Nothing in the array has to start at zero.  All calls on one GPU share
+ * the array: calls that overlap on one GPU (different streams, or threads) race; calls on one stream do not.
+ */
+#define KV_ATTN_SCRATCH_BYTES (8u << 20)
+int kv_decode_attn_static(const kv_plan_t *plan, const kv_view_t *kv, int layer, const void *q, void *out,
+                          int out_dtype, int n_splits, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------ */
 /* Chunk pipeline (blocking; returns after the drain)                                         */
 /* ------------------------------------------------------------------------------------------ */

@@ -28,6 +28,7 @@ KV_KERNEL_PACK, KV_KERNEL_UNPACK, KV_KERNEL_ATTN_PARTIAL, KV_KERNEL_ATTN_COMBINE
 KV_PIPE_TIME_KERNELS = 1
 KV_PIPE_SERIALIZE = 2
 KV_PIPE_ATTN_FROM_EXTENT = 4
+KV_ATTN_SCRATCH_BYTES = 8 << 20
 KV_COPY_AUTO, KV_COPY_MEMCPY, KV_COPY_KERNEL = 0, 1, 2
 KV_ORDER_CROSS, KV_ORDER_INTRA = 0, 1
 
@@ -36,7 +37,7 @@ EXPORTS = [
     "kv_plan_translate", "kv_plan_chunk_cmds", "kv_plan_range_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
     "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
-    "kv_abi_sizeof", "kv_budget_sample",
+    "kv_abi_sizeof", "kv_budget_sample", "kv_decode_attn_static",
 ]
 
 
@@ -133,6 +134,7 @@ def lib() -> C.CDLL:
         L.kv_offload_pack.argtypes = [vp, i, i, C.POINTER(kv_view_t), i, i, i, vp, C.c_size_t, vp]
         L.kv_reload_unpack.argtypes = [vp, i, i, vp, C.c_size_t, C.POINTER(kv_view_t), i, i, i, vp]
         L.kv_decode_attn.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp, C.c_size_t, vp]
+        L.kv_decode_attn_static.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp]
         L.kv_decode_attn_workspace.argtypes = [vp, i, i]
         L.kv_decode_attn_workspace.restype = C.c_size_t
         L.kv_pipeline_run.argtypes = [vp, i, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t, i, i,
@@ -343,6 +345,13 @@ def kv_decode_attn(plan: Plan, kv: View, layer: int, q, out, out_dtype: int, n_s
     _check(lib().kv_decode_attn(plan.handle, kv.ref(), layer, q.data_ptr(), out.data_ptr(), out_dtype, n_splits,
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 _stream_ptr(stream)), "kv_decode_attn")
+
+
+def kv_decode_attn_static(plan: Plan, kv: View, layer: int, q, out, out_dtype: int, n_splits: int = 0,
+                          stream=None) -> None:
+    """kv_decode_attn without a workspace argument: the library's own static device array holds the partials."""
+    _check(lib().kv_decode_attn_static(plan.handle, kv.ref(), layer, q.data_ptr(), out.data_ptr(), out_dtype,
+                                       n_splits, _stream_ptr(stream)), "kv_decode_attn_static")
 
 
 # ------------------------------------------------------------------------------------------ pipeline

@@ -18,6 +18,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "plan.hpp"
 
@@ -517,8 +518,11 @@ extern "C" size_t kv_decode_attn_workspace(const kv_plan_t *p, int n_splits, int
     return (size_t)p->B * p->Hq * ns * (p->D + 2) * sizeof(float);
 }
 
-extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *q, void *out,
-                              int out_dtype, int n_splits, void *workspace, size_t ws_bytes, void *hip_stream)
+namespace {
+
+// Checks, split choice and the two launches; shared by both entry points.  Allocates nothing.
+int decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *q, void *out, int out_dtype,
+                int n_splits, void *workspace, size_t ws_bytes, void *hip_stream)
 {
     if (!p || !kv || !q || !out || !workspace) return KV_EINVAL;
     if (out_dtype != KV_OUT_F32 && out_dtype != KV_OUT_SAME) return KV_EINVAL;
@@ -613,4 +617,43 @@ extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
     return KV_OK;
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, resolved on the first call there
+
+}  // namespace
+
+// Split partials of kv_decode_attn_static: every GPU the library runs on holds its own copy of this array
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[KV_ATTN_SCRATCH_BYTES];
+
+extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *q, void *out,
+                              int out_dtype, int n_splits, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    return decode_attn(p, kv, layer, q, out, out_dtype, n_splits, workspace, ws_bytes, hip_stream);
+}
+
+extern "C" int kv_decode_attn_static(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *q, void *out,
+                                     int out_dtype, int n_splits, void *hip_stream)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
+    if (dev < 0 || dev >= kMaxDevices) return KV_EINVAL;
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> g(g_scratch_mu);
+        if (!g_scratch_ptr[dev]) {
+            // the array's name is a host-side stand-in; its device address on the current GPU is looked up once
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) { kvb::set_hip_error((int)e); return KV_EHIP; }
+            g_scratch_ptr[dev] = ptr;
+        }
+        ws = g_scratch_ptr[dev];
+    }
+    // decode_attn answers KV_ENOSPC when the partials of this call do not fit the array
+    return decode_attn(p, kv, layer, q, out, out_dtype, n_splits, ws, (size_t)KV_ATTN_SCRATCH_BYTES, hip_stream);
 }
