@@ -45,19 +45,12 @@ struct SegTable {
     Seg seg[kMaxSegs];
 };
 
-template <bool NT>
-__device__ __forceinline__ u32x4 ld(const u32x4 *p)
-{
-    return NT ? __builtin_nontemporal_load(p) : *p;
-}
-template <bool NT>
-__device__ __forceinline__ void st(u32x4 *p, u32x4 v)
-{
-    if (NT) __builtin_nontemporal_store(v, p); else *p = v;
-}
+// Every byte is touched once: nontemporal loads and stores keep the streams out of each other's way in L2.
+__device__ __forceinline__ u32x4 ld(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
 
 // PACK: source -> image.  !PACK: image -> source.  U = token rows in flight per thread.
-template <bool PACK, bool PAGED, int U, bool NTL, bool NTS>
+template <bool PACK, bool PAGED, int U>
 __global__ void __launch_bounds__(kThreads)
 kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, int rx_log2, int tpb, int rchunk)
 {
@@ -133,7 +126,7 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const unsigned long long i = sg.img_off + (unsigned long long)(t0 + u * TY) * rowv + r;
-                if (ok[u]) v[u] = PACK ? ld<NTL>(base + a[u]) : ld<NTL>(img + i);
+                if (ok[u]) v[u] = PACK ? ld(base + a[u]) : ld(img + i);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -142,9 +135,9 @@ kv_layout_kernel(SrcDesc s, u32x4 *__restrict__ img, SegTable segs, int rowv, in
                     // a skipped block id still owns its bytes of the image: they read as zero
                     const bool in = (t0 + u * TY) < t_end;
                     const u32x4 z = {0u, 0u, 0u, 0u};
-                    if (in) st<NTS>(img + i, ok[u] ? v[u] : z);
+                    if (in) st(img + i, ok[u] ? v[u] : z);
                 } else if (ok[u]) {
-                    st<NTS>(base + a[u], v[u]);
+                    st(base + a[u], v[u]);
                 }
             }
         }
@@ -238,22 +231,12 @@ Shape pick_shape(bool pack, bool paged, int rowv, unsigned long long launch_byte
     return Shape{5, 8, 64 * 1024, 32 * 1024};
 }
 
-// Measurement override: fields > 0 (rx_cap >= 0) replace the table's.
-Shape g_force{-1, 0, 0, 0};
-bool g_nt_load = true, g_nt_store = true;
-
 template <bool PACK, bool PAGED, int U>
 void launch_nt(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv, int rx_log2,
                int tpb, int rchunk)
 {
-    u32x4 *im = (u32x4 *)img;
-    if (g_nt_load) {
-        if (g_nt_store) hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, true, true>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb, rchunk);
-        else hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, true, false>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb, rchunk);
-    } else {
-        if (g_nt_store) hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, false, true>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb, rchunk);
-        else hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U, false, false>), grid, dim3(kThreads), 0, stream, s, im, tab, rowv, rx_log2, tpb, rchunk);
-    }
+    hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U>), grid, dim3(kThreads), 0, stream, s, (u32x4 *)img, tab, rowv,
+                       rx_log2, tpb, rchunk);
 }
 
 template <bool PACK, bool PAGED>
@@ -272,11 +255,7 @@ int launch(const kv_plan *p, const kv_view_t *v, const Seg *segs, int nseg, void
     const bool paged = v->layout == KV_LAYOUT_PAGED;
     unsigned long long launch_bytes = 0;
     for (int i = 0; i < nseg; ++i) launch_bytes += (unsigned long long)segs[i].ntok * p->row_bytes;
-    Shape sh = pick_shape(PACK, paged, rowv, launch_bytes);
-    if (g_force.rx_cap >= 0) sh.rx_cap = g_force.rx_cap;
-    if (g_force.unroll > 0) sh.unroll = g_force.unroll;
-    if (g_force.tile_bytes > 0) sh.tile_bytes = g_force.tile_bytes;
-    if (g_force.run_bytes > 0) sh.run_bytes = g_force.run_bytes;
+    const Shape sh = pick_shape(PACK, paged, rowv, launch_bytes);
     int rx_log2 = 0;
     while ((1 << rx_log2) < rowv && rx_log2 < sh.rx_cap) ++rx_log2;
     const int TY = kThreads >> rx_log2;
@@ -425,17 +404,6 @@ int pack_last_rows(const kv_plan *p, const kv_view_t *v, int layer_begin, int la
             }
     }
     return launch<true>(p, v, segs.data(), (int)segs.size(), dst, stream);
-}
-
-// Measurement hook (not part of the C ABI): launch shape of the pack / unpack kernels.
-void set_layout_tuning(int tile_bytes, int unroll, bool nt_load, bool nt_store, int run_bytes, int rx_cap)
-{
-    g_force.tile_bytes = tile_bytes >= 1024 ? tile_bytes : 0;
-    g_force.unroll = (unroll == 2 || unroll == 4 || unroll == 8) ? unroll : 0;
-    g_force.run_bytes = run_bytes >= 16 ? run_bytes : 0;
-    g_force.rx_cap = (rx_cap >= 0 && rx_cap <= 8) ? rx_cap : -1;
-    g_nt_load = nt_load;
-    g_nt_store = nt_store;
 }
 }
 
