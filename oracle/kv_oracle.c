@@ -9,6 +9,11 @@
  * It shares no code with the GPU library and is only used by the tests, the smoke
  * check and the CPU-baseline leg of the benchmark.
  *
+ * The defining build is plain C, one thread (what every test uses).  The same file compiled
+ * with -fopenmp is the all-core timing variant of the benchmark's CPU baseline: the loops over
+ * tokens (pack / unpack) and over (b, h_q) (attention) are then shared among the threads; the
+ * arithmetic of every output element is the same statement sequence in both builds.
+ *
  * Pins (tests/test_oracle_*.py): sizes the paper prints (Table 2, Sec. III request
  * sizes and KV totals, Sec. V-A device parameters), the three bind invariants, brute
  * force sector sets on tiny shapes, NumPy transposes for the byte order, closed forms
@@ -29,6 +34,22 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#define ORC_PARALLEL_FOR _Pragma("omp parallel for schedule(static)")
+#else
+#define ORC_PARALLEL_FOR
+#endif
+
+/* Threads the loops of this build are shared among (1 in the defining build). */
+int orc_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 #define ORC_OK 0
 #define ORC_EINVAL (-1)
@@ -244,6 +265,7 @@ void orc_pack(const orc_src_t *v, const uint16_t *src, int per_seq, int64_t B, c
     uint16_t *out = (uint16_t *)ext;
     if (!per_seq) {
         int64_t S = len[0];
+        ORC_PARALLEL_FOR
         for (int64_t s = 0; s < S; ++s)
             for (int64_t b = 0; b < B; ++b)
                 for (int64_t h = 0; h < H; ++h)
@@ -255,6 +277,7 @@ void orc_pack(const orc_src_t *v, const uint16_t *src, int per_seq, int64_t B, c
     }
     for (int64_t b = 0; b < B; ++b) {
         uint16_t *sub = (uint16_t *)(ext + seq_base[b] * lba_size);
+        ORC_PARALLEL_FOR
         for (int64_t s = 0; s < len[b]; ++s)
             for (int64_t h = 0; h < H; ++h)
                 for (int64_t d = 0; d < D; ++d)
@@ -273,6 +296,7 @@ void orc_unpack(const orc_src_t *v, uint16_t *dst, int per_seq, int64_t B, const
     const uint16_t *in = (const uint16_t *)ext;
     if (!per_seq) {
         int64_t S = len[0];
+        ORC_PARALLEL_FOR
         for (int64_t s = 0; s < S; ++s)
             for (int64_t b = 0; b < B; ++b)
                 for (int64_t h = 0; h < H; ++h)
@@ -282,6 +306,7 @@ void orc_unpack(const orc_src_t *v, uint16_t *dst, int per_seq, int64_t B, const
     }
     for (int64_t b = 0; b < B; ++b) {
         const uint16_t *sub = (const uint16_t *)(ext + seq_base[b] * lba_size);
+        ORC_PARALLEL_FOR
         for (int64_t s = 0; s < len[b]; ++s)
             for (int64_t h = 0; h < H; ++h)
                 for (int64_t d = 0; d < D; ++d)
@@ -328,38 +353,37 @@ int orc_attention(const orc_src_t *v, const uint16_t *K, const uint16_t *V, cons
     if (Hq % H != 0) return ORC_EINVAL;
     int64_t G = Hq / H;
     double (*dec)(uint16_t) = is_bf16 ? orc_bf16_to_double : orc_f16_to_double;
-    int64_t max_len = 0;
-    for (int64_t b = 0; b < B; ++b)
-        if (len[b] > max_len) max_len = len[b];
-    double *s = (double *)malloc(sizeof(double) * (size_t)(max_len > 0 ? max_len : 1));
-    if (!s) return ORC_EINVAL;
-    for (int64_t b = 0; b < B; ++b) {
-        for (int64_t hq = 0; hq < Hq; ++hq) {
-            int64_t h = hq / G;
-            double *o = out + (b * Hq + hq) * D;
-            for (int64_t d = 0; d < D; ++d) o[d] = 0.0;
-            int64_t n = len[b];
-            if (n == 0) continue;
-            double m = -INFINITY;
-            for (int64_t j = 0; j < n; ++j) {
-                double dot = 0.0;
-                for (int64_t d = 0; d < D; ++d)
-                    dot += dec(q[(b * Hq + hq) * D + d]) * dec(K[src_index(v, b, h, j, d)]);
-                s[j] = dot / sqrt((double)D);
-                if (s[j] > m) m = s[j];
-            }
-            double denom = 0.0;
-            for (int64_t j = 0; j < n; ++j) {
-                s[j] = exp(s[j] - m);
-                denom += s[j];
-            }
-            for (int64_t j = 0; j < n; ++j) {
-                double p = s[j] / denom;
-                for (int64_t d = 0; d < D; ++d)
-                    o[d] += p * dec(V[src_index(v, b, h, j, d)]);
-            }
+    int failed = 0;
+    /* every (b, hq) is independent: its own score buffer, its own output row */
+    ORC_PARALLEL_FOR
+    for (int64_t bh = 0; bh < B * Hq; ++bh) {
+        int64_t b = bh / Hq, hq = bh % Hq;
+        int64_t h = hq / G;
+        double *o = out + (b * Hq + hq) * D;
+        for (int64_t d = 0; d < D; ++d) o[d] = 0.0;
+        int64_t n = len[b];
+        if (n == 0) continue;
+        double *s = (double *)malloc(sizeof(double) * (size_t)n);
+        if (!s) { failed = 1; continue; }
+        double m = -INFINITY;
+        for (int64_t j = 0; j < n; ++j) {
+            double dot = 0.0;
+            for (int64_t d = 0; d < D; ++d)
+                dot += dec(q[(b * Hq + hq) * D + d]) * dec(K[src_index(v, b, h, j, d)]);
+            s[j] = dot / sqrt((double)D);
+            if (s[j] > m) m = s[j];
         }
+        double denom = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            s[j] = exp(s[j] - m);
+            denom += s[j];
+        }
+        for (int64_t j = 0; j < n; ++j) {
+            double p = s[j] / denom;
+            for (int64_t d = 0; d < D; ++d)
+                o[d] += p * dec(V[src_index(v, b, h, j, d)]);
+        }
+        free(s);
     }
-    free(s);
-    return ORC_OK;
+    return failed ? ORC_EINVAL : ORC_OK;
 }

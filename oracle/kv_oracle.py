@@ -2,8 +2,15 @@
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this.
 It marshals NumPy arrays to the plain C definitions and composes them into a whole
-layout plan and a whole-cache pack; it contains no arithmetic of its own beyond
-multiplying shapes into byte counts.
+layout plan (Alg. 1 then Eq. 3-6).  Arithmetic of its own, each pinned in
+tests/test_oracle_plan.py: byte counts from shapes (`Plan.row_bytes`, `region_bytes`,
+`pageable_bytes`), the byte offset of an extent in its host buffer (`ext_byte_off`), and the
+first sector handed to Alg. 2 by `token_range` (start LBA on the direct path; arena byte
+offset / sector size on the page-cache path; plus the sequence's base in per-sequence mode).
+
+`omp=True` on pack / unpack / attention runs the all-core build of the same C file (the
+benchmark's second CPU-baseline figure); everything else, and every test of the GPU path,
+uses the defining one-thread build.
 """
 from __future__ import annotations
 
@@ -22,12 +29,16 @@ _LIB = os.path.join(_HERE, "libkv_oracle.so")
 OK, EINVAL, EALIGN, ERANGE = 0, -1, -2, -3
 
 
-def build(force: bool = False) -> str:
-    """Compile kv_oracle.c with gcc (plain -O2, one thread)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
-                               "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+_LIB_OMP = os.path.join(_HERE, "libkv_oracle_omp.so")
+
+
+def build(force: bool = False, omp: bool = False) -> str:
+    """Compile kv_oracle.c with gcc: plain -O2, one thread (the defining build), or the same with -fopenmp."""
+    out = _LIB_OMP if omp else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra"]
+                              + (["-fopenmp"] if omp else []) + ["-o", out, _SRC, "-lm"])
+    return out
 
 
 class _Src(C.Structure):
@@ -37,48 +48,61 @@ class _Src(C.Structure):
                 ("block_tokens", C.c_int64), ("H", C.c_int64), ("D", C.c_int64)]
 
 
-_lib = None
+_libs = {}
 
 
-def lib():
-    global _lib
-    if _lib is None:
-        _lib = C.CDLL(build())
-        _lib.orc_residency.restype = C.c_int64
-        _lib.orc_residency.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_void_p]
-        _lib.orc_tensor_blocks.restype = C.c_int
-        _lib.orc_tensor_blocks.argtypes = [C.c_int, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
-                                           C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
-        _lib.orc_bind.restype = None
-        _lib.orc_bind.argtypes = [C.c_int64, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64,
-                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-        _lib.orc_translate.restype = C.c_int
-        _lib.orc_translate.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
-                                       C.c_void_p, C.c_void_p]
-        _lib.orc_chunk_size.restype = C.c_uint64
-        _lib.orc_chunk_size.argtypes = [C.c_uint64, C.c_uint64]
-        _lib.orc_chunk_cmds.restype = C.c_int64
-        _lib.orc_chunk_cmds.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_int64,
-                                        C.c_void_p, C.c_void_p, C.c_void_p]
-        _lib.orc_pack.restype = None
-        _lib.orc_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
-                                  C.c_uint64, C.c_uint64, C.c_void_p]
-        _lib.orc_unpack.restype = None
-        _lib.orc_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
-                                    C.c_uint64, C.c_void_p]
-        _lib.orc_attention.restype = C.c_int
-        _lib.orc_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int64,
-                                       C.c_int64, C.c_void_p, C.c_void_p]
-        _lib.orc_budget.restype = None
-        _lib.orc_budget.argtypes = [C.c_int64] * 5 + [C.c_void_p, C.c_void_p]
-        _lib.orc_trim.restype = None
-        _lib.orc_trim.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64]
-        _lib.orc_adapt_order.restype = C.c_int
-        _lib.orc_adapt_order.argtypes = [C.c_int64, C.c_double, C.c_double]
-        _lib.orc_f16_to_double.restype = C.c_double
-        _lib.orc_f16_to_double.argtypes = [C.c_uint16]
-        _lib.orc_bf16_to_double.restype = C.c_double
-        _lib.orc_bf16_to_double.argtypes = [C.c_uint16]
+def lib(omp: bool = False):
+    if omp not in _libs:
+        # KV_ORACLE_LIB names another build of kv_oracle.c (e.g. one instrumented by sanitizers) for the one-thread role
+        other = None if omp else os.environ.get("KV_ORACLE_LIB")
+        _libs[omp] = _load(other or build(omp=omp))
+    return _libs[omp]
+
+
+def threads(omp: bool = False) -> int:
+    """Threads the loops of that build are shared among (1 for the defining build)."""
+    return int(lib(omp).orc_threads())
+
+
+def _load(path):
+    _lib = C.CDLL(path)
+    _lib.orc_threads.restype = C.c_int
+    _lib.orc_threads.argtypes = []
+    _lib.orc_residency.restype = C.c_int64
+    _lib.orc_residency.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_void_p]
+    _lib.orc_tensor_blocks.restype = C.c_int
+    _lib.orc_tensor_blocks.argtypes = [C.c_int, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                       C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+    _lib.orc_bind.restype = None
+    _lib.orc_bind.argtypes = [C.c_int64, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64,
+                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _lib.orc_translate.restype = C.c_int
+    _lib.orc_translate.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
+                                   C.c_void_p, C.c_void_p]
+    _lib.orc_chunk_size.restype = C.c_uint64
+    _lib.orc_chunk_size.argtypes = [C.c_uint64, C.c_uint64]
+    _lib.orc_chunk_cmds.restype = C.c_int64
+    _lib.orc_chunk_cmds.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_int64,
+                                    C.c_void_p, C.c_void_p, C.c_void_p]
+    _lib.orc_pack.restype = None
+    _lib.orc_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
+                              C.c_uint64, C.c_uint64, C.c_void_p]
+    _lib.orc_unpack.restype = None
+    _lib.orc_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
+                                C.c_uint64, C.c_void_p]
+    _lib.orc_attention.restype = C.c_int
+    _lib.orc_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int64,
+                                   C.c_int64, C.c_void_p, C.c_void_p]
+    _lib.orc_budget.restype = None
+    _lib.orc_budget.argtypes = [C.c_int64] * 5 + [C.c_void_p, C.c_void_p]
+    _lib.orc_trim.restype = None
+    _lib.orc_trim.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64]
+    _lib.orc_adapt_order.restype = C.c_int
+    _lib.orc_adapt_order.argtypes = [C.c_int64, C.c_double, C.c_double]
+    _lib.orc_f16_to_double.restype = C.c_double
+    _lib.orc_f16_to_double.argtypes = [C.c_uint16]
+    _lib.orc_bf16_to_double.restype = C.c_double
+    _lib.orc_bf16_to_double.argtypes = [C.c_uint16]
     return _lib
 
 
@@ -202,33 +226,33 @@ def u16(t) -> np.ndarray:
 
 
 def pack(src: Source, data: np.ndarray, per_seq: bool, lens: Sequence[int], seq_base: np.ndarray,
-         n_blocks: int, lba_size: int, ext: np.ndarray) -> None:
+         n_blocks: int, lba_size: int, ext: np.ndarray, omp: bool = False) -> None:
     """Write one tensor's whole extent (payload + zero pad) into ext (uint8, n_blocks*lba_size)."""
     assert ext.dtype == np.uint8 and ext.flags.c_contiguous and ext.size >= n_blocks * lba_size
     lens = np.asarray(lens, dtype=np.int32)
     seq_base = np.ascontiguousarray(seq_base, dtype=np.uint64)
     s = src.c()
-    lib().orc_pack(C.byref(s), _p(data), int(per_seq), len(lens), _p(lens), _p(seq_base), n_blocks, lba_size, _p(ext))
+    lib(omp).orc_pack(C.byref(s), _p(data), int(per_seq), len(lens), _p(lens), _p(seq_base), n_blocks, lba_size, _p(ext))
 
 
 def unpack(src: Source, data: np.ndarray, per_seq: bool, lens: Sequence[int], seq_base: np.ndarray,
-           lba_size: int, ext: np.ndarray) -> None:
+           lba_size: int, ext: np.ndarray, omp: bool = False) -> None:
     assert ext.dtype == np.uint8 and ext.flags.c_contiguous and data.flags.writeable
     lens = np.asarray(lens, dtype=np.int32)
     seq_base = np.ascontiguousarray(seq_base, dtype=np.uint64)
     s = src.c()
-    lib().orc_unpack(C.byref(s), _p(data), int(per_seq), len(lens), _p(lens), _p(seq_base), lba_size, _p(ext))
+    lib(omp).orc_unpack(C.byref(s), _p(data), int(per_seq), len(lens), _p(lens), _p(seq_base), lba_size, _p(ext))
 
 
 def attention(src: Source, K: np.ndarray, V: np.ndarray, q: np.ndarray, is_bf16: bool,
-              lens: Sequence[int], Hq: int) -> np.ndarray:
+              lens: Sequence[int], Hq: int, omp: bool = False) -> np.ndarray:
     """One decode-attention step in double.  q is uint16 [B,Hq,D]; returns float64 [B,Hq,D]."""
     lens = np.asarray(lens, dtype=np.int32)
     B = len(lens)
     out = np.zeros((B, Hq, src.D), dtype=np.float64)
     s = src.c()
     q = np.ascontiguousarray(q)
-    rc = lib().orc_attention(C.byref(s), _p(K), _p(V), _p(q), int(is_bf16), B, Hq, _p(lens), _p(out))
+    rc = lib(omp).orc_attention(C.byref(s), _p(K), _p(V), _p(q), int(is_bf16), B, Hq, _p(lens), _p(out))
     if rc:
         raise ValueError(rc)
     return out

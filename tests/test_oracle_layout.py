@@ -161,3 +161,33 @@ def test_chunk_slices_tile_the_extent():
             covered[c_slba * sec:(c_slba + nlb + 1) * sec] += 1
     assert (covered[:2048 * sec] == 0).all()                   # the hole below lba_start is never addressed
     assert (covered[2048 * sec:] == 1).all()
+
+
+def test_all_core_build_equals_the_defining_build():
+    """The -fopenmp build of the same file (the benchmark's all-core timing variant) must give the same bytes and
+    the same doubles as the one-thread build every other test uses."""
+    rng = np.random.default_rng(5)
+    B, H, S, D, sec = 3, 2, 37, 64, 512
+    data = rng.integers(0, 65536, size=(B, H, S, D), dtype=np.uint16)
+    src = o.bhsd_source(data.shape)
+    for per_seq, lens in ((False, [S] * B), (True, [37, 5, 20])):
+        nb, base, _ = o.tensor_blocks(per_seq, lens, H, D, 2, sec)
+        a = np.full(nb * sec, 0xEE, dtype=np.uint8)
+        b = np.full(nb * sec, 0xEE, dtype=np.uint8)
+        o.pack(src, data, per_seq, lens, base, nb, sec, a)
+        o.pack(src, data, per_seq, lens, base, nb, sec, b, omp=True)
+        assert np.array_equal(a, b)
+        back_a = np.zeros_like(data)
+        back_b = np.zeros_like(data)
+        o.unpack(src, back_a, per_seq, lens, base, sec, a)
+        o.unpack(src, back_b, per_seq, lens, base, sec, a, omp=True)
+        assert np.array_equal(back_a, back_b)
+    import torch
+    K = torch.randn((B, H, S, D), generator=torch.Generator().manual_seed(3)).to(torch.bfloat16)
+    V = torch.randn((B, H, S, D), generator=torch.Generator().manual_seed(4)).to(torch.bfloat16)
+    q = torch.randn((B, 4, D), generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
+    lens = [37, 0, 20]
+    one = o.attention(src, o.u16(K), o.u16(V), o.u16(q), True, lens, 4)
+    many = o.attention(src, o.u16(K), o.u16(V), o.u16(q), True, lens, 4, omp=True)
+    assert np.array_equal(one, many)
+    assert o.threads(False) == 1 and o.threads(True) >= 1

@@ -246,6 +246,44 @@ def test_token_range_helper_matches_alg2():
             assert req == 8 * 256
 
 
+def test_token_range_on_the_pagecache_path_is_the_arena_sector():
+    """A page-cache-path tensor has no LBA: Alg. 2 is fed the sector index of its arena offset, so the closed form
+    is file_off / sector + seq_base + tok0 * row_bytes / sector, with the tensors before it fixing file_off."""
+    sec, H, D, caps = 512, 2, 64, [300, 100, 257]
+    row = H * D * 2                                            # 256 bytes per token row of a sequence
+    blocks = [-(-c * row // sec) for c in caps]                # per-sequence sub-extents, each padded to a sector
+    tensor_bytes = sum(blocks) * sec
+    X = 2 * 2 * tensor_bytes                                   # room for exactly two layers on the page-cache path
+    p = o.layout_plan(4, H, 4, D, caps, 2, sec, True, X, 2048)
+    assert p.n1 == 2 and list(p.path) == [1, 1, 1, 1, 0, 0, 0, 0]
+    for n in range(4):                                         # arena tensors, in id order from offset 0
+        assert int(p.file_off[n]) == n * tensor_bytes and int(p.lba_start[n]) == 0
+        for b in range(3):
+            rc, sector, req = o.token_range(p, n, b, 4, 8)
+            assert rc == o.OK and req == 8 * row
+            assert sector == n * tensor_bytes // sec + sum(blocks[:b]) + 4 * row // sec
+    for n in range(4, 8):                                      # direct tensors: LBAs from the user's start, arena skipped
+        rc, slba, _ = o.token_range(p, n, 1, 2, 2)
+        assert rc == o.OK and slba == 2048 + (n - 4) * sum(blocks) + blocks[0] + 2 * row // sec
+    # token-major twin: one extent (S_cap, B*H, D)
+    q = o.layout_plan(2, 2, 4, 64, [64, 64], 2, 512, False, 2 * 64 * 2 * 2 * 64 * 2, 7)
+    assert q.n1 == 1
+    assert o.token_range(q, 1, 0, 3, 2) == (o.OK, 64 * 512 // 512 + 3, 2 * 512)     # second arena tensor, row = 512 B
+    assert o.token_range(q, 2, 0, 3, 2) == (o.OK, 7 + 3, 2 * 512)                   # first direct tensor
+
+
+def test_plan_byte_helpers_closed_forms():
+    """row_bytes, region_bytes, pageable_bytes and ext_byte_off against sizes worked out by hand."""
+    p = o.layout_plan(3, 2, 4, 64, [100, 100], 2, 512, False, 2 * 51200, 10)        # row = 2*2*64*2 = 512 B
+    assert p.row_bytes == 512 and p.n_blocks_tensor == 100 and p.n1 == 1
+    assert p.pageable_bytes == 2 * 51200                       # K and V of layer 0
+    assert p.region_bytes == (10 + 4 * 100) * 512              # hole below LBA 10, then four direct tensors
+    assert [p.ext_byte_off(n) for n in range(6)] == [0, 51200, 10 * 512, 110 * 512, 210 * 512, 310 * 512]
+    assert p.direct_blocks == 400
+    r = o.layout_plan(1, 2, 4, 64, [3, 5], 2, 512, True, 0, 0)                      # per sequence: row = 256 B
+    assert r.row_bytes == 256 and list(r.seq_base) == [0, 2] and r.n_blocks_tensor == 2 + 3
+
+
 # ------------------------------------------------------------------ Eq. 1-2
 def test_budget_closed_forms():
     GB = 10**9
