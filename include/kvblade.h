@@ -184,6 +184,9 @@ typedef struct kv_pipe_opts {
     uint64_t max_cmd_bytes;  /* transfer-size limit of one command (MDTS of Eq. 7), 0 = none: a chunk larger than
                                 align_down(max_cmd_bytes, sector) moves as several commands of at most that
                                 size (Eq. 8-11 on the chunk), each counted against depth */
+    void *caller_stream;     /* hipStream_t on which the caller produced (or still reads) the view's buffers, the
+                                queries and the block table; NULL = the default stream.  The library's own streams
+                                are ordered after everything queued on it when the call is entered */
 } kv_pipe_opts_t;
 
 typedef struct kv_pipe_stats {
@@ -339,6 +342,12 @@ int kv_decode_attn_static(const kv_plan_t *plan, const kv_view_t *kv, int layer,
  * pageable_bytes_needed if any page-cache-path layer is in range.  chunk_tokens 0 = the plan's.
  * The library owns its streams, events, staging slots, bounce ring and worker threads (created on
  * first use per plan, freed by kv_plan_destroy).  Calls on one plan must not overlap.
+ * Stream order: the kernels and copies run on the library's streams.  On entry these are ordered after all
+ * work already queued on opts->caller_stream (the default stream when opts or the field is NULL), so KV rows,
+ * queries and block tables written by kernels on that stream are complete before the first pack or attention
+ * launch reads them, and kernels still reading the view finish before an unpack overwrites it.  Work on any
+ * other stream must be complete (or ordered before caller_stream) when the call is made.  The call returns
+ * after its last kernel and copy have finished, so results are visible to every stream afterwards.
  * stats: host, may be NULL.
  */
 int kv_pipeline_run(kv_plan_t *plan, int dir, int layer_begin, int layer_end, const kv_view_t *view,
@@ -357,7 +366,11 @@ int kv_pipeline_run(kv_plan_t *plan, int dir, int layer_begin, int layer_end, co
  * reads that sector back (counted in n_rmw_reads), later appends use the image the library keeps;
  * bytes after the row up to the sector end are written as zeros (no later row exists yet).
  * Blocking.  lba_region / pageable as in kv_pipeline_run (pinned-ness is not required here).
- * kv_pipeline_run(KV_DIR_OFFLOAD) forgets the kept sector images.
+ * The kept sector images are forgotten by kv_pipeline_run(KV_DIR_OFFLOAD), by kv_plan_trim, and whenever a call
+ * names another lba_region or pageable base address than the one the images were taken from; they assume that
+ * only this library writes the extents in between.
+ * caller_stream: hipStream_t on which the new rows of the view were produced (NULL = the default stream); the
+ * pack of the rows is ordered after everything queued on it at entry.
  */
 typedef struct kv_append_stats {
     uint32_t n_cmds;         /* write commands (one per tensor and sequence) */
@@ -365,7 +378,8 @@ typedef struct kv_append_stats {
     uint64_t blocks_written; /* sectors written */
 } kv_append_stats_t;
 int kv_append_tokens(kv_plan_t *plan, int layer_begin, int layer_end, const kv_view_t *view, void *lba_region,
-                     size_t region_bytes, void *pageable, size_t pageable_bytes, kv_append_stats_t *stats);
+                     size_t region_bytes, void *pageable, size_t pageable_bytes, void *caller_stream,
+                     kv_append_stats_t *stats);
 
 /*
  * kv_budget -- Eq. 1-2, the page-cache budget the knob X of kv_layout_plan is drawn from:
@@ -376,7 +390,7 @@ int kv_budget(int64_t m_avail, int64_t m_max, int64_t m_anon_shmem, int32_t n_th
               int64_t *m_star, int64_t *b_pc);
 
 /*
- * kv_budget_sample -- the three memory figures of Eq. 1 "under system and cgroup limits" (Sec. IV-A "Plan"),
+ * kv_budget_sample -- the three memory figures of Eq. 1 (Sec. IV-A "Plan": system-wide and cgroup limits),
  * sampled now on this Linux host, in bytes: M_avail = MemAvailable of /proc/meminfo; M_max = the memory limit of
  * this process's cgroup (cgroup v2 memory.max, else v1 memory.limit_in_bytes), or MemTotal when there is no
  * limit; M_anon+shmem = anon + shmem of the cgroup's memory.stat (v1: rss + shmem) when it has a limit, else
@@ -391,6 +405,7 @@ int kv_budget_sample(const char *root, int64_t *m_avail, int64_t *m_max, int64_t
  * host-memory model a deallocated block reads back as zeros: the extent bytes in lba_region (direct
  * path) or pageable (page-cache path) are cleared.  *n_ranges, *n_blocks (nullable) count the ranges
  * and sectors released.  KV_ENOSPC if a buffer does not cover an extent; nothing is written then.
+ * The sector images kv_append_tokens keeps for this plan are forgotten (the sectors now read zeros).
  */
 int kv_plan_trim(const kv_plan_t *plan, int layer_begin, int layer_end, void *lba_region, size_t region_bytes,
                  void *pageable, size_t pageable_bytes, uint64_t *n_ranges, uint64_t *n_blocks);

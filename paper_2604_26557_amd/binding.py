@@ -12,7 +12,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libkvblade.so")
+# KVBLADE_LIB names another build of the same library (e.g. one whose host code is instrumented by sanitizers)
+LIB_PATH = os.environ.get("KVBLADE_LIB") or os.path.join(_PKG, "libkvblade.so")
 
 KV_OK, KV_EINVAL, KV_EALIGN, KV_ERANGE, KV_ENOSPC, KV_EHIP = 0, -1, -2, -3, -4, -5
 KV_F16, KV_BF16 = 0, 1
@@ -88,7 +89,8 @@ class kv_attn_args_t(C.Structure):
 class kv_pipe_opts_t(C.Structure):
     _fields_ = [("span_chunks", C.c_int32), ("host_workers", C.c_int32), ("flags", C.c_uint32),
                 ("copy_streams", C.c_int32), ("d2h_mode", C.c_int32), ("h2d_mode", C.c_int32),
-                ("order_pagecache", C.c_int32), ("order_direct", C.c_int32), ("max_cmd_bytes", C.c_uint64)]
+                ("order_pagecache", C.c_int32), ("order_direct", C.c_int32), ("max_cmd_bytes", C.c_uint64),
+                ("caller_stream", C.c_void_p)]
 
 
 class kv_pipe_stats_t(C.Structure):
@@ -140,7 +142,7 @@ def lib() -> C.CDLL:
         L.kv_pipeline_run.argtypes = [vp, i, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t, i, i,
                                       C.POINTER(kv_attn_args_t), C.POINTER(kv_pipe_opts_t),
                                       C.POINTER(kv_pipe_stats_t)]
-        L.kv_append_tokens.argtypes = [vp, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t,
+        L.kv_append_tokens.argtypes = [vp, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t, vp,
                                        C.POINTER(kv_append_stats_t)]
         L.kv_budget.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.POINTER(C.c_int64),
                                 C.POINTER(C.c_int64)]
@@ -322,18 +324,26 @@ def _stream_ptr(stream) -> Optional[int]:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+def _caller_stream(stream) -> Optional[int]:
+    """The stream handed to the blocking calls: the given one, else PyTorch's current stream."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return _stream_ptr(stream)
+
+
 # ------------------------------------------------------------------------------------------ kernels
 def kv_offload_pack(plan: Plan, layer: int, kind: int, src: View, seq: int, tok0: int, ntok: int, dst,
                     stream=None) -> None:
     """dst: torch uint8 device tensor receiving the bytes."""
     _check(lib().kv_offload_pack(plan.handle, layer, kind, src.ref(), seq, tok0, ntok, dst.data_ptr(),
-                                 dst.numel() * dst.element_size(), _stream_ptr(stream)), "kv_offload_pack")
+                                 dst.numel() * dst.element_size(), _caller_stream(stream)), "kv_offload_pack")
 
 
 def kv_reload_unpack(plan: Plan, layer: int, kind: int, src, dst: View, seq: int, tok0: int, ntok: int,
                      stream=None) -> None:
     _check(lib().kv_reload_unpack(plan.handle, layer, kind, src.data_ptr(), src.numel() * src.element_size(),
-                                  dst.ref(), seq, tok0, ntok, _stream_ptr(stream)), "kv_reload_unpack")
+                                  dst.ref(), seq, tok0, ntok, _caller_stream(stream)), "kv_reload_unpack")
 
 
 def kv_decode_attn_workspace(plan: Plan, n_splits: int, max_len: int) -> int:
@@ -344,14 +354,14 @@ def kv_decode_attn(plan: Plan, kv: View, layer: int, q, out, out_dtype: int, n_s
                    stream=None) -> None:
     _check(lib().kv_decode_attn(plan.handle, kv.ref(), layer, q.data_ptr(), out.data_ptr(), out_dtype, n_splits,
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                _stream_ptr(stream)), "kv_decode_attn")
+                                _caller_stream(stream)), "kv_decode_attn")
 
 
 def kv_decode_attn_static(plan: Plan, kv: View, layer: int, q, out, out_dtype: int, n_splits: int = 0,
                           stream=None) -> None:
     """kv_decode_attn without a workspace argument: the library's own static device array holds the partials."""
     _check(lib().kv_decode_attn_static(plan.handle, kv.ref(), layer, q.data_ptr(), out.data_ptr(), out_dtype,
-                                       n_splits, _stream_ptr(stream)), "kv_decode_attn_static")
+                                       n_splits, _caller_stream(stream)), "kv_decode_attn_static")
 
 
 # ------------------------------------------------------------------------------------------ pipeline
@@ -362,8 +372,10 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
                     copy_streams: int = 0, d2h_mode: int = KV_COPY_AUTO, h2d_mode: int = KV_COPY_AUTO,
                     serialize: bool = False, attn_from_extent: bool = False,
                     order_pagecache: int = KV_ORDER_CROSS, order_direct: int = KV_ORDER_CROSS,
-                    max_cmd_bytes: int = 0) -> kv_pipe_stats_t:
-    """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array."""
+                    max_cmd_bytes: int = 0, stream=None) -> kv_pipe_stats_t:
+    """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array.
+    stream: the stream the view's buffers were produced on (default: PyTorch's current stream); the library
+    orders its own streams after it."""
     def host(buf):
         if buf is None:
             return None, 0
@@ -381,7 +393,7 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
         keep = (qa, oa)
     opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0)
                           | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0), copy_streams,
-                          d2h_mode, h2d_mode, order_pagecache, order_direct, max_cmd_bytes)
+                          d2h_mode, h2d_mode, order_pagecache, order_direct, max_cmd_bytes, _caller_stream(stream))
     st = kv_pipe_stats_t()
     rc = lib().kv_pipeline_run(plan.handle, direction, layer_begin, layer_end, view.ref(), rp, rb, pp, pb,
                                chunk_tokens, depth, C.byref(attn) if attn is not None else None, C.byref(opts),
@@ -400,12 +412,12 @@ def _host_buf(buf):
 
 
 def kv_append_tokens(plan: Plan, layer_begin: int, layer_end: int, view: View, lba_region=None,
-                     pageable=None) -> kv_append_stats_t:
+                     pageable=None, stream=None) -> kv_append_stats_t:
     rp, rb = _host_buf(lba_region)
     pp, pb = _host_buf(pageable)
     st = kv_append_stats_t()
-    _check(lib().kv_append_tokens(plan.handle, layer_begin, layer_end, view.ref(), rp, rb, pp, pb, C.byref(st)),
-           "kv_append_tokens")
+    _check(lib().kv_append_tokens(plan.handle, layer_begin, layer_end, view.ref(), rp, rb, pp, pb,
+                                  _caller_stream(stream), C.byref(st)), "kv_append_tokens")
     return st
 
 

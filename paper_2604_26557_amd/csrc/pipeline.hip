@@ -195,6 +195,8 @@ struct kv_pipeline {
     size_t append_host_bytes = 0;
     std::vector<char> tail_img;
     std::vector<int64_t> tail_sector;
+    const void *tail_region = nullptr, *tail_pageable = nullptr;  // host buffers the images were taken from
+    hipEvent_t ev_entry = nullptr;  // orders the library's streams after the caller's stream at call entry
 
     ~kv_pipeline()
     {
@@ -207,6 +209,7 @@ struct kv_pipeline {
         for (auto e : ev_done) (void)hipEventDestroy(e);
         for (auto &e : ring) if (e.ev) (void)hipEventDestroy(e.ev);
         for (auto e : timing) (void)hipEventDestroy(e);
+        if (ev_entry) (void)hipEventDestroy(ev_entry);
         if (staging) (void)hipFree(staging);
         if (bounce) (void)hipHostFree(bounce);
         if (append_host) (void)hipHostFree(append_host);
@@ -237,6 +240,7 @@ int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, si
         KV_HIP(hipGetDevice(&p->pipe->device));
         KV_HIP(hipStreamCreateWithFlags(&p->pipe->s_compute, hipStreamNonBlocking));
         for (auto &st : p->pipe->s_copy) KV_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        KV_HIP(hipEventCreateWithFlags(&p->pipe->ev_entry, hipEventDisableTiming));
     }
     kv_pipeline *q = p->pipe;
     const size_t need = n_slots * slot_bytes;
@@ -400,6 +404,16 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
     return KV_OK;
 }
 
+// The kernels of a call read (or overwrite) buffers the caller produced on its own stream: order the kernel
+// stream after everything queued there so far.  The copy streams only follow the kernel stream (offload) or
+// touch library-owned staging (reload), so this one edge is enough.
+int order_after_caller(kv_pipeline *q, void *caller_stream)
+{
+    KV_HIP(hipEventRecord(q->ev_entry, (hipStream_t)caller_stream));
+    KV_HIP(hipStreamWaitEvent(q->s_compute, q->ev_entry, 0));
+    return KV_OK;
+}
+
 inline void spin_until_zero(std::atomic<int> &a)
 {
     int spins = 0;
@@ -409,6 +423,11 @@ inline void spin_until_zero(std::atomic<int> &a)
 }
 
 }  // namespace
+
+void kvb::forget_tail_images(kv_pipeline *pipe)
+{
+    std::fill(pipe->tail_sector.begin(), pipe->tail_sector.end(), (int64_t)-1);
+}
 
 extern "C" void kv_plan_destroy(kv_plan_t *plan)
 {
@@ -528,6 +547,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     int rc = ensure_pipeline(p, n_slots, slot_bytes, (int)NB, bounce_slot, any_pc, n_workers, ws_bytes, n_timing);
     if (rc != KV_OK) return rc;
     kv_pipeline *q = p->pipe;
+    rc = order_after_caller(q, opts ? opts->caller_stream : nullptr);
+    if (rc != KV_OK) return rc;
     if (attn_from_extent && p->mode == KV_PER_SEQ && !q->seq_off_dev) {
         q->seq_off_host.resize((size_t)p->B);
         for (int b = 0; b < p->B; ++b) q->seq_off_host[b] = (int64_t)(p->seq_base[b] * sec / 2);
@@ -550,7 +571,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     };
 
     const bool offload = offload_dir;
-    if (offload) std::fill(q->tail_sector.begin(), q->tail_sector.end(), (int64_t)-1);  // extents are rewritten
+    if (offload) kvb::forget_tail_images(q);  // extents are rewritten
     const size_t N = chunks.size();
     std::vector<unsigned> slot_used(n_slots, 0u);  // copy streams that carried the slot's last span
     size_t n_waited = 0;  // chunks [0, n_waited) are known complete
@@ -818,7 +839,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
 // ------------------------------------------------------------------------------------------------
 // Decode append.
 extern "C" int kv_append_tokens(kv_plan_t *p, int layer_begin, int layer_end, const kv_view_t *view, void *lba_region,
-                                size_t region_bytes, void *pageable, size_t pageable_bytes, kv_append_stats_t *stats)
+                                size_t region_bytes, void *pageable, size_t pageable_bytes, void *caller_stream,
+                                kv_append_stats_t *stats)
 {
     if (!p || !view || !view->seq_lens_host) return KV_EINVAL;
     if (layer_begin < 0 || layer_end > p->L || layer_begin > layer_end || layer_end > view->n_layers) return KV_ERANGE;
@@ -852,6 +874,12 @@ extern "C" int kv_append_tokens(kv_plan_t *p, int layer_begin, int layer_end, co
         q->tail_sector.assign(n_entries, -1);
         q->tail_img.assign(n_entries * sec, 0);
     }
+    // images taken from other host buffers say nothing about these
+    if ((any_direct && q->tail_region != lba_region) || (any_pc && q->tail_pageable != pageable)) kvb::forget_tail_images(q);
+    if (any_direct) q->tail_region = lba_region;
+    if (any_pc) q->tail_pageable = pageable;
+    rc = order_after_caller(q, caller_stream);
+    if (rc != KV_OK) return rc;
 
     // GPU side: the new row of every tensor (and sequence) in extent order, then one transfer
     rc = kvb::pack_last_rows(p, view, layer_begin, layer_end, q->staging, q->staging_bytes, q->s_compute);

@@ -390,6 +390,7 @@ extern "C" int kv_plan_trim(const kv_plan_t *p, int layer_begin, int layer_end, 
             }
         }
     }
+    if (p->pipe && ranges > 0) kvb::forget_tail_images(p->pipe);  // those sectors now read zeros
     if (n_ranges) *n_ranges = ranges;
     if (n_blocks) *n_blocks = blocks;
     return KV_OK;
@@ -463,4 +464,4 @@ extern "C" const char *kv_strerror(int code)
     }
 }
 
-extern "C" int kv_abi_version(void) { return 2; }
+extern "C" int kv_abi_version(void) { return 3; }

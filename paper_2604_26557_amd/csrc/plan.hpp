@@ -9,7 +9,7 @@
 
 #include "kvblade.h"
 
-struct kv_pipeline;  // pipeline.cpp
+struct kv_pipeline;  // pipeline.hip
 
 struct kv_plan {
     int32_t L, H, Hq, D, B, dtype, sector, chunk_tokens, mode;
@@ -57,6 +57,9 @@ int range_cmds(const kv_plan *p, int layer, int kind, int seq, int tok0, int nto
                std::vector<kv_cmd_t> *out);
 
 void set_hip_error(int e);
+
+// pipeline.hip: the decode append's kept tail-sector images are no longer valid (extents rewritten or trimmed)
+void forget_tail_images(kv_pipeline *pipe);
 
 // layout_kernels.hip
 int pack_last_rows(const kv_plan *p, const kv_view_t *v, int layer_begin, int layer_end, void *dst, size_t dst_bytes,

@@ -622,6 +622,84 @@ def test_decode_append(cfg):
     assert e.value.code == kv.KV_ERANGE
 
 
+def test_append_after_trim_and_after_a_change_of_region():
+    """The kept tail-sector image must not outlive the bytes it mirrors: after kv_plan_trim the sector reads zeros,
+    and another region buffer holds whatever it holds.  offload, append, trim, append / append into a copy."""
+    cfg = APPEND_CONFIGS[0]
+    case = Case(cfg, "cuda", gen_device="cpu", cap_extra=2)
+    r, L = case.ref, cfg.n_layers
+    FILL = 0x99
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, L, case.view, region, arena, depth=2)
+    lens1 = [n + 1 for n in case.lens]
+    st = kv.kv_append_tokens(case.plan, 0, L, case.make_view(case.k, case.v, lens1), region, arena)
+    assert (((lens1[0] - 1) * r.row_bytes) % r.lba_size != 0) == (st.n_rmw_reads > 0)
+    # a second region with the same bytes: the images were taken from `region`, so the library reads this one back
+    region2 = pinned_bytes(r.region_bytes, FILL)
+    region2.copy_(region)
+    arena2 = arena.copy()
+    lens2 = [n + 1 for n in lens1]
+    kv.kv_append_tokens(case.plan, 0, L, case.make_view(case.k, case.v, lens2), region2, arena2)
+    want_region, want_arena = case.expected_host(fill=FILL, lens=lens2)
+    assert np.array_equal(region2.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena2[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    # trim: every extent reads zeros; the next append merges with zeros, not with the rows written before
+    kv.kv_plan_trim(case.plan, 0, L, region2, arena2)
+    kv.kv_append_tokens(case.plan, 0, L, case.make_view(case.k, case.v, lens2), region2, arena2)
+    got_region, got_arena = region2.numpy(), arena2
+    row, sec = r.row_bytes, r.lba_size
+    nseq = len(lens2) if r.per_seq else 1
+    for n in range(2 * L):
+        buf = got_region if r.path[n] == 0 else got_arena
+        ext = buf[r.ext_byte_off(n):r.ext_byte_off(n) + r.n_blocks_tensor * sec]
+        want = np.zeros_like(ext)
+        full = case.expected_extent(n // 2, n % 2, lens=lens2)
+        for b in range(nseq):                      # only the appended row of each (sub-)extent is non-zero
+            base = int(r.seq_base[b]) * sec if r.per_seq else 0
+            a = base + (lens2[b] - 1) * row
+            want[a:a + row] = full[a:a + row]
+        assert np.array_equal(ext, want), n
+
+
+def test_pipeline_waits_for_the_callers_stream():
+    """KV written by kernels on a side stream, offloaded without any device-wide synchronisation: the library's
+    streams must be ordered after the caller's stream (kv_pipe_opts_t.caller_stream), so the host bytes are the
+    checker's pack of the final values, not of what the buffers held before."""
+    cfg = W.shrink(W.CONFIGS[1], n_layers=2, seq_len=2048)
+    case = Case(cfg, "cuda", gen_device="cpu")
+    r, L = case.ref, cfg.n_layers
+    FILL = 0x42
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    final_k = [t.clone() for t in case.k]
+    final_v = [t.clone() for t in case.v]
+    for t in case.k + case.v:
+        t.zero_()                                   # what a racing pack would pick up
+    big = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(200):                        # tens of milliseconds of queued work ahead of the writes
+            big.add_(1)
+        for dst, src in zip(case.k + case.v, final_k + final_v):
+            dst.copy_(src)
+        kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, L, case.view, region, arena, depth=3)
+    want_region, want_arena = case.expected_host(fill=FILL)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+    # reload into buffers that a kernel on the side stream is still filling: the unpack must come after it
+    k_new, v_new = case.blank_like_source()
+    with torch.cuda.stream(side):
+        for _ in range(200):
+            big.add_(1)
+        for t in k_new + v_new:
+            t.fill_(1.0)
+        kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, L, case.make_view(k_new, v_new), region, arena, depth=3)
+    for l in range(L):
+        assert np.array_equal(bits(k_new[l]), bits(case.k_cpu[l])) and np.array_equal(bits(v_new[l]), bits(case.v_cpu[l]))
+
+
 def test_many_sequences_span_several_launches():
     """70 ragged per-sequence sub-extents per tensor: the pack / unpack segment table holds 32 runs, so one tensor
     takes several launches; the append packs 140 rows.  Host bytes, round trip and append against the checker."""
