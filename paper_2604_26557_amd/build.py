@@ -53,6 +53,31 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_sanitized(outdir: str) -> str:
+    """The same sources with the HOST code instrumented by AddressSanitizer and UndefinedBehaviorSanitizer
+    (device code is compiled as usual and not instrumented): for CPU runs of the planner and the host logic.
+    The result links against clang's shared sanitizer runtime, which the process that loads it must preload."""
+    os.makedirs(outdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = ["-O1", "-g"] + [f for f in FLAGS if f != "-O3"]
+    procs = []
+    for src in sources():
+        obj = os.path.join(outdir, os.path.basename(src) + ".o")
+        procs.append((obj, subprocess.Popen([HIPCC, *flags, *san, "-c", src, "-o", obj],
+                                            stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    objs = []
+    for obj, pr in procs:
+        out, _ = pr.communicate()
+        if pr.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {obj}:\n{out}")
+        objs.append(obj)
+    lib = os.path.join(outdir, "libkvblade_san.so")
+    subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-Xarch_host", "-fsanitize=address",
+                           "-Xarch_host", "-fsanitize=undefined", "-shared-libsan", "-o", lib, *objs, "-lpthread"])
+    return lib
+
+
 def build_if_missing() -> str:
     """For harnesses (tests, smoke, bench): build only when no library has been built.  The binding itself
     never builds and never falls back: it raises when the library is missing."""
