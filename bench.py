@@ -148,16 +148,22 @@ def cpu_baseline(cfg, W, budget_s: float = 24.0, gpu_attn=None):
 
 
 def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens, reps: int):
-    """Resident-KV leg: every kernel of the path launched back to back on whole layers, rotating over
-    all layers (so each launch touches memory no earlier launch left in the last-level cache), no DMA
-    in flight.  Each kind is bracketed by events on the stream it is launched on (the default stream,
-    which is also PyTorch's current stream here); the figure is the average per launch, gaps included."""
+    """Resident-KV leg: every kernel of the path launched back to back in the launch configuration the pipeline
+    uses (K and V of a layer in one launch up to 256 MiB; consecutive layers of one path together while their
+    images stay within 128 MiB), rotating over all layers (so each launch touches memory no earlier launch left
+    in the last-level cache), no DMA in flight.  Each kind is bracketed by events on the stream it is launched on
+    (the default stream, which is also PyTorch's current stream here); the figure is the average per launch,
+    gaps included."""
     L = cfg.n_layers
+    n1 = int(info.n_pagecache_layers)
     tensor_image = int(info.tensor_blocks) * cfg.sector_bytes
-    pair = 2 * tensor_image <= (256 << 20)                # the pipeline's rule: K and V share a launch up to 256 MiB
-    kinds = [kv.KV_KV] if pair else [kv.KV_K, kv.KV_V]
-    image = (2 if pair else 1) * tensor_image
-    n_img = max(2, min(L * len(kinds), (1 << 30) // image))   # rotating extent images, about 1 GiB
+    pair = 2 * tensor_image <= (256 << 20)
+    group = min(16, max(1, (128 << 20) // (2 * tensor_image))) if pair else 1
+    runs = []                                             # (first layer, layers) of every launch; a run keeps to one path
+    for lo, hi in ((0, n1), (n1, L)):
+        runs += [(l, min(group, hi - l)) for l in range(lo, hi, group)]
+    image = (2 * group if pair else 1) * tensor_image
+    n_img = max(2, min(len(runs) * (1 if pair else 2), (1 << 30) // image))   # rotating extent images, about 1 GiB
     imgs = [torch.empty(image, dtype=torch.uint8, device="cuda") for _ in range(n_img)]
     max_len = max(lens)
     ws = torch.empty(kv.kv_decode_attn_workspace(plan, 0, max_len), dtype=torch.uint8, device="cuda")
@@ -174,19 +180,27 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / (reps * n_launches)   # microseconds per launch
 
-    def pack_all():      # the launches the pipeline issues: whole tensors, or K and V of a layer together
+    def pack_all():
         i = 0
-        for l in range(L):
-            for kind in kinds:
-                kv.kv_offload_pack(plan, l, kind, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[i % n_img])
+        for l, n in runs:
+            if n > 1:
+                kv.kv_offload_pack_layers(plan, l, l + n, src_view, imgs[i % n_img])
                 i += 1
+            else:
+                for kind in ([kv.KV_KV] if pair else [kv.KV_K, kv.KV_V]):
+                    kv.kv_offload_pack(plan, l, kind, src_view, kv.KV_SEQ_ALL, 0, 0, imgs[i % n_img])
+                    i += 1
 
     def unpack_all():
         i = 0
-        for l in range(L):
-            for kind in kinds:
-                kv.kv_reload_unpack(plan, l, kind, imgs[i % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
+        for l, n in runs:
+            if n > 1:
+                kv.kv_reload_unpack_layers(plan, l, l + n, imgs[i % n_img], dst_view)
                 i += 1
+            else:
+                for kind in ([kv.KV_KV] if pair else [kv.KV_K, kv.KV_V]):
+                    kv.kv_reload_unpack(plan, l, kind, imgs[i % n_img], dst_view, kv.KV_SEQ_ALL, 0, 0)
+                    i += 1
 
     def attn_all():
         for l in range(L):
@@ -198,9 +212,9 @@ def kernel_leg(torch, kv, cfg, plan, info, src_view, dst_view, k, qs, outs, lens
         for i in range(8):
             imgs[(i + 1) % n_img].copy_(imgs[i % n_img])
 
-    n = L * len(kinds)
+    n = len(runs) * (1 if pair else 2)
     return {"pack_us": timed(pack_all, n), "unpack_us": timed(unpack_all, n), "attn_us": timed(attn_all, L),
-            "copy_ref_us": timed(copy_ref, 8), "copy_ref_bytes": image, "tensors_per_launch": 2 // len(kinds),
+            "copy_ref_us": timed(copy_ref, 8), "copy_ref_bytes": image, "tensors_per_launch": 2 * L / n,
             "layout_launches": n}
 
 

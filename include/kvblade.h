@@ -170,8 +170,9 @@ typedef struct kv_attn_args {
 #define KV_ORDER_INTRA 1 /* K's and V's commands alternate: both tensors' storage-side hops run side by side */
 
 typedef struct kv_pipe_opts {
-    int32_t span_chunks;  /* chunks of one tensor per kernel launch and staging slot; 0 = a whole layer
-                             (K and V in one launch) */
+    int32_t span_chunks;  /* chunks of one tensor per kernel launch and staging slot; 0 = whole extents: K and V
+                             of a layer in one launch, and consecutive layers of one path together while their
+                             images stay within 128 MiB (a launch must be tens of MiB to run at HBM speed) */
     int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
     uint32_t flags;       /* KV_PIPE_* */
     int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (3 for the copy kernel,
@@ -292,6 +293,19 @@ int kv_offload_pack(const kv_plan_t *plan, int layer, int kind, const kv_view_t 
  */
 int kv_reload_unpack(const kv_plan_t *plan, int layer, int kind, const void *src_dev, size_t src_bytes,
                      const kv_view_t *dst, int seq, int tok0, int ntok, void *hip_stream);
+
+/*
+ * kv_offload_pack_layers / kv_reload_unpack_layers -- the whole extent images (as kv_offload_pack with
+ * seq = KV_SEQ_ALL) of K and V of layers [layer_begin, layer_end), back to back in tensor-id order (layer
+ * ascending, K before V; the id chain of Sec. IV-B "LBA Bind"): tensor (l, kind) at byte
+ * ((l - layer_begin)*2 + kind) * n_blocks*sector of dst_dev / src_dev.  All tensors share launches (a layer of a
+ * few MiB alone is too short a launch to reach HBM speed).  Same rules and errors as the single-tensor calls;
+ * dst_bytes / src_bytes >= (layer_end - layer_begin) * 2 * n_blocks*sector, else KV_ENOSPC.
+ */
+int kv_offload_pack_layers(const kv_plan_t *plan, int layer_begin, int layer_end, const kv_view_t *src,
+                           void *dst_dev, size_t dst_bytes, void *hip_stream);
+int kv_reload_unpack_layers(const kv_plan_t *plan, int layer_begin, int layer_end, const void *src_dev,
+                            size_t src_bytes, const kv_view_t *dst, void *hip_stream);
 
 /*
  * kv_decode_attn -- one decode-attention step of one layer over resident KV (Sec. II-A: similarity of

@@ -38,7 +38,7 @@ EXPORTS = [
     "kv_plan_translate", "kv_plan_chunk_cmds", "kv_plan_range_cmds", "kv_offload_pack", "kv_reload_unpack", "kv_decode_attn",
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
     "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
-    "kv_abi_sizeof", "kv_budget_sample", "kv_decode_attn_static",
+    "kv_abi_sizeof", "kv_budget_sample", "kv_decode_attn_static", "kv_offload_pack_layers", "kv_reload_unpack_layers",
 ]
 
 
@@ -135,6 +135,8 @@ def lib() -> C.CDLL:
         L.kv_plan_range_cmds.argtypes = [vp, i, i, i, i, i, C.c_uint64, C.POINTER(kv_cmd_t), i, C.POINTER(i)]
         L.kv_offload_pack.argtypes = [vp, i, i, C.POINTER(kv_view_t), i, i, i, vp, C.c_size_t, vp]
         L.kv_reload_unpack.argtypes = [vp, i, i, vp, C.c_size_t, C.POINTER(kv_view_t), i, i, i, vp]
+        L.kv_offload_pack_layers.argtypes = [vp, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp]
+        L.kv_reload_unpack_layers.argtypes = [vp, i, i, vp, C.c_size_t, C.POINTER(kv_view_t), vp]
         L.kv_decode_attn.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp, C.c_size_t, vp]
         L.kv_decode_attn_static.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp]
         L.kv_decode_attn_workspace.argtypes = [vp, i, i]
@@ -344,6 +346,18 @@ def kv_reload_unpack(plan: Plan, layer: int, kind: int, src, dst: View, seq: int
                      stream=None) -> None:
     _check(lib().kv_reload_unpack(plan.handle, layer, kind, src.data_ptr(), src.numel() * src.element_size(),
                                   dst.ref(), seq, tok0, ntok, _caller_stream(stream)), "kv_reload_unpack")
+
+
+def kv_offload_pack_layers(plan: Plan, layer_begin: int, layer_end: int, src: View, dst, stream=None) -> None:
+    _check(lib().kv_offload_pack_layers(plan.handle, layer_begin, layer_end, src.ref(), dst.data_ptr(),
+                                        dst.numel() * dst.element_size(), _caller_stream(stream)),
+           "kv_offload_pack_layers")
+
+
+def kv_reload_unpack_layers(plan: Plan, layer_begin: int, layer_end: int, src, dst: View, stream=None) -> None:
+    _check(lib().kv_reload_unpack_layers(plan.handle, layer_begin, layer_end, src.data_ptr(),
+                                         src.numel() * src.element_size(), dst.ref(), _caller_stream(stream)),
+           "kv_reload_unpack_layers")
 
 
 def kv_decode_attn_workspace(plan: Plan, n_splits: int, max_len: int) -> int:

@@ -232,7 +232,7 @@ Shape pick_shape(bool pack, bool paged, int rowv, unsigned long long launch_byte
 }
 
 template <bool PACK, bool PAGED, int U>
-void launch_nt(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv, int rx_log2,
+void launch_k(dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv, int rx_log2,
                int tpb, int rchunk)
 {
     hipLaunchKernelGGL((kv_layout_kernel<PACK, PAGED, U>), grid, dim3(kThreads), 0, stream, s, (u32x4 *)img, tab, rowv,
@@ -243,9 +243,9 @@ template <bool PACK, bool PAGED>
 void launch_u(int U, dim3 grid, hipStream_t stream, const SrcDesc &s, void *img, const SegTable &tab, int rowv,
               int rx_log2, int tpb, int rchunk)
 {
-    if (U == 8) launch_nt<PACK, PAGED, 8>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
-    else if (U == 2) launch_nt<PACK, PAGED, 2>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
-    else launch_nt<PACK, PAGED, 4>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
+    if (U == 8) launch_k<PACK, PAGED, 8>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
+    else if (U == 2) launch_k<PACK, PAGED, 2>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
+    else launch_k<PACK, PAGED, 4>(grid, stream, s, img, tab, rowv, rx_log2, tpb, rchunk);
 }
 
 template <bool PACK>
@@ -293,6 +293,70 @@ int launch(const kv_plan *p, const kv_view_t *v, const Seg *segs, int nseg, void
     return KV_OK;
 }
 
+// Runs of the whole extent image of tensor (layer, which) placed at byte img_off of the image buffer: rows
+// [0, len_b) of every sequence and the zero pad up to each (sub-)extent's end.
+int whole_extent_segs(const kv_plan *p, const kv_view_t *v, int layer, int which, uint64_t img_off, std::vector<Seg> *segs)
+{
+    const uint64_t sec = (uint64_t)p->sector;
+    const uint64_t image = p->tensor_blocks * sec;
+    if (p->mode == KV_TOKEN_MAJOR) {
+        const int len = v->seq_lens_host[0];
+        for (int b = 0; b < p->B; ++b)
+            if (v->seq_lens_host[b] != len) return KV_EINVAL;
+        if (len < 0 || len > p->cap[0]) return KV_ERANGE;
+        int rc = check_rows(p, v, -1, 0, len);
+        if (rc != KV_OK) return rc;
+        Seg s{};
+        s.img_off = img_off / 16;
+        s.b = -1; s.tok0 = 0; s.ntok = len; s.base = tensor_base(v, layer, which);
+        s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
+        s.pad_vecs = (unsigned)((image - (uint64_t)len * p->row_bytes) / 16);
+        segs->push_back(s);
+        return KV_OK;
+    }
+    for (int b = 0; b < p->B; ++b) {
+        const int len = v->seq_lens_host[b];
+        if (len < 0 || len > p->cap[b]) return KV_ERANGE;
+        int rc = check_rows(p, v, b, 0, len);
+        if (rc != KV_OK) return rc;
+        const uint64_t sub_bytes = kvb::round_up((uint64_t)p->cap[b] * p->row_bytes, sec);
+        Seg s{};
+        s.img_off = (img_off + p->seq_base[b] * sec) / 16;
+        s.b = b; s.tok0 = 0; s.ntok = len; s.base = tensor_base(v, layer, which);
+        s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
+        s.pad_vecs = (unsigned)((sub_bytes - (uint64_t)len * p->row_bytes) / 16);
+        if (len > 0 || s.pad_vecs > 0) segs->push_back(s);
+    }
+    return KV_OK;
+}
+
+// Whole extent images of K and V of layers [layer_begin, layer_end), back to back in tensor-id order (layer
+// ascending, K before V), in as few launches as the segment table allows: a small layer alone is too short a
+// launch to reach HBM speed.
+template <bool PACK>
+int run_layers(const kv_plan *p, int layer_begin, int layer_end, const kv_view_t *v, void *img, size_t img_bytes,
+               void *hip_stream)
+{
+    if (!p || !img || ((uintptr_t)img & 15)) return KV_EINVAL;
+    if (layer_begin < 0 || layer_end > p->L || layer_begin > layer_end) return KV_ERANGE;
+    if (p->row_bytes / 16 > (uint64_t)INT_MAX) return KV_EINVAL;
+    const uint64_t image = p->tensor_blocks * (uint64_t)p->sector;
+    if (img_bytes < (uint64_t)(layer_end - layer_begin) * 2 * image) return KV_ENOSPC;
+    std::vector<Seg> segs;
+    for (int l = layer_begin; l < layer_end; ++l) {
+        int rc = check_view(p, v, l);
+        if (rc != KV_OK) return rc;
+        for (int w = 0; w < 2; ++w) {
+            rc = whole_extent_segs(p, v, l, w, ((uint64_t)(l - layer_begin) * 2 + (uint64_t)w) * image, &segs);
+            if (rc != KV_OK) return rc;
+        }
+    }
+    if (!PACK)
+        for (Seg &s : segs) s.pad_vecs = 0;
+    if (segs.empty()) return KV_OK;
+    return launch<PACK>(p, v, segs.data(), (int)segs.size(), img, (hipStream_t)hip_stream);
+}
+
 template <bool PACK>
 int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int tok0, int ntok, void *img,
         size_t img_bytes, void *hip_stream)
@@ -313,37 +377,9 @@ int run(const kv_plan *p, int layer, int kind, const kv_view_t *v, int seq, int 
         // Whole extent image(s).
         const uint64_t image = p->tensor_blocks * sec;
         if (img_bytes < n_img * image) return KV_ENOSPC;
-        if (p->mode == KV_TOKEN_MAJOR) {
-            const int len = v->seq_lens_host[0];
-            for (int b = 0; b < p->B; ++b)
-                if (v->seq_lens_host[b] != len) return KV_EINVAL;
-            if (len < 0 || len > p->cap[0]) return KV_ERANGE;
-            rc = check_rows(p, v, -1, 0, len);
+        for (int w = first; w <= last; ++w) {
+            rc = whole_extent_segs(p, v, layer, w, (uint64_t)(w - first) * image, &segs);
             if (rc != KV_OK) return rc;
-            for (int w = first; w <= last; ++w) {
-                Seg s{};
-                s.img_off = (uint64_t)(w - first) * image / 16;
-                s.b = -1; s.tok0 = 0; s.ntok = len; s.base = tensor_base(v, layer, w);
-                s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
-                s.pad_vecs = (unsigned)((image - (uint64_t)len * p->row_bytes) / 16);
-                segs.push_back(s);
-            }
-        } else {
-            for (int w = first; w <= last; ++w) {
-                for (int b = 0; b < p->B; ++b) {
-                    const int len = v->seq_lens_host[b];
-                    if (len < 0 || len > p->cap[b]) return KV_ERANGE;
-                    rc = check_rows(p, v, b, 0, len);
-                    if (rc != KV_OK) return rc;
-                    const uint64_t sub_bytes = kvb::round_up((uint64_t)p->cap[b] * p->row_bytes, sec);
-                    Seg s{};
-                    s.img_off = ((uint64_t)(w - first) * image + p->seq_base[b] * sec) / 16;
-                    s.b = b; s.tok0 = 0; s.ntok = len; s.base = tensor_base(v, layer, w);
-                    s.pad_off = s.img_off + (uint64_t)len * p->row_bytes / 16;
-                    s.pad_vecs = (unsigned)((sub_bytes - (uint64_t)len * p->row_bytes) / 16);
-                    if (len > 0 || s.pad_vecs > 0) segs.push_back(s);
-                }
-            }
         }
     } else {
         kvb::RowRange r;
@@ -417,4 +453,16 @@ extern "C" int kv_reload_unpack(const kv_plan_t *plan, int layer, int kind, cons
                                 const kv_view_t *dst, int seq, int tok0, int ntok, void *hip_stream)
 {
     return run<false>(plan, layer, kind, dst, seq, tok0, ntok, const_cast<void *>(src_dev), src_bytes, hip_stream);
+}
+
+extern "C" int kv_offload_pack_layers(const kv_plan_t *plan, int layer_begin, int layer_end, const kv_view_t *src,
+                                      void *dst_dev, size_t dst_bytes, void *hip_stream)
+{
+    return run_layers<true>(plan, layer_begin, layer_end, src, dst_dev, dst_bytes, hip_stream);
+}
+
+extern "C" int kv_reload_unpack_layers(const kv_plan_t *plan, int layer_begin, int layer_end, const void *src_dev,
+                                       size_t src_bytes, const kv_view_t *dst, void *hip_stream)
+{
+    return run_layers<false>(plan, layer_begin, layer_end, dst, const_cast<void *>(src_dev), src_bytes, hip_stream);
 }

@@ -156,6 +156,7 @@ struct Chunk {
     uint64_t bytes;      // (nlb + 1) * sector
     int span;
     bool first, last;    // first / last chunk of its span
+    int layer, kind;     // the tensor the command belongs to
 };
 
 struct Span {
@@ -163,7 +164,13 @@ struct Span {
     uint64_t bytes;                    // image bytes
     int path;
     bool last_of_layer;
+    int n_layers;                      // > 1: whole K and V images of layers [layer, layer + n_layers), one launch
 };
+
+// Layers one whole-extent span may cover: as many as keep the images within 128 MiB (a launch of a few MiB is
+// mostly ramp: 16 MiB per launch ran at half the HBM rate of 128 MiB), at most 16.
+constexpr uint64_t kGroupBytes = 128ull << 20;
+constexpr int kGroupLayersMax = 16;
 
 struct Entry {
     hipEvent_t ev = nullptr;
@@ -305,31 +312,39 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
     // or alternating (KV_ORDER_INTRA: both tensors' hops proceed side by side) -- the two overlap
     // strategies of Sec. IV-C.
     struct Unit { Span span; std::vector<Chunk> chunks; };
-    for (int l = layer_begin; l < layer_end; ++l) {
+    for (int l = layer_begin; l < layer_end;) {
         const int order = l < p->n1 ? order_pc : order_direct;
         // Whole-extent spans: K and V of a layer share one launch while the pair stays within 256 MiB
         // (measured: pairing gains ~5 % at 64 MiB tensors and loses ~10 % at 256 MiB tensors), or when
-        // their chunks alternate.
+        // their chunks alternate.  Small layers go together: consecutive layers of one path share a span
+        // (K then V per layer, so the command stream stays one ascending run).
         const bool pair = span_chunks == 0 && (2 * image <= (256ull << 20) || order == KV_ORDER_INTRA);
+        int group = 1;
+        if (pair && order == KV_ORDER_CROSS) {
+            const int path_end = l < p->n1 ? std::min(p->n1, layer_end) : layer_end;
+            group = (int)std::min<uint64_t>(kGroupLayersMax, std::max<uint64_t>(1, kGroupBytes / (2 * image)));
+            group = std::min(group, path_end - l);
+        }
         std::vector<Unit> units[2];
+        for (int lg = l; lg < l + group; ++lg)
         for (int kind = 0; kind < 2; ++kind) {
-            const kv_extent_t &ext = p->ext[2 * l + kind];
+            const kv_extent_t &ext = p->ext[2 * lg + kind];
             const int nseq = p->mode == KV_TOKEN_MAJOR ? 1 : p->B;
-            if (span_chunks == 0) {
+            if (span_chunks == 0 && lg == l) {
                 Unit u;
-                u.span = pair ? Span{l, KV_KV, KV_SEQ_ALL, 0, 0, 2 * image, ext.path, false}
-                              : Span{l, kind, KV_SEQ_ALL, 0, 0, image, ext.path, false};
+                u.span = pair ? Span{l, KV_KV, KV_SEQ_ALL, 0, 0, (uint64_t)group * 2 * image, ext.path, false, group}
+                              : Span{l, kind, KV_SEQ_ALL, 0, 0, image, ext.path, false, 1};
                 units[kind].push_back(u);
             }
             for (int b = 0; b < nseq; ++b) {
-                int rc = kvb::chunk_cmds(p, l, kind, b, (int)C, &cmds);
+                int rc = kvb::chunk_cmds(p, lg, kind, b, (int)C, &cmds);
                 if (rc != KV_OK) return rc;
                 for (size_t i = 0; i < cmds.size(); ++i) {
                     const kv_cmd_t &c = cmds[i];
                     if (span_chunks > 0 && i % (size_t)span_chunks == 0) {
                         const size_t j = std::min(cmds.size(), i + (size_t)span_chunks) - 1;
                         Unit u;
-                        u.span = Span{l, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false};
+                        u.span = Span{lg, kind, b, (int)c.tok0, (int)(cmds[j].tok0 + cmds[j].ntok - c.tok0), 0, ext.path, false, 1};
                         for (size_t k = i; k <= j; ++k) u.span.bytes += ((uint64_t)cmds[k].nlb + 1) * sec;
                         units[kind].push_back(u);
                     }
@@ -338,9 +353,11 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
                     ch.host_off = c.slba * sec;
                     ch.bytes = ((uint64_t)c.nlb + 1) * sec;
                     ch.span = -1;
-                    ch.stage_off = span_chunks == 0 ? (pair ? (uint64_t)kind * image : 0) + p->seq_base[b] * sec + c.buf_off
+                    ch.stage_off = span_chunks == 0 ? (pair ? ((uint64_t)(lg - l) * 2 + (uint64_t)kind) * image : 0) + p->seq_base[b] * sec + c.buf_off
                                                     : c.buf_off - (uint64_t)u.span.tok0 * p->row_bytes;
                     ch.first = ch.last = false;
+                    ch.layer = lg;
+                    ch.kind = kind;
                     const uint64_t host_cap = ext.path == KV_PATH_DIRECT ? region_bytes : pageable_bytes;
                     if (ch.host_off + ch.bytes > host_cap) return KV_ENOSPC;
                     // transfer-size limit: Eq. 8-11 once more on the chunk's own request
@@ -357,17 +374,22 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
         auto emit_span = [&](const Span &sp) { spans.push_back(sp); return (int)spans.size() - 1; };
         auto emit_chunk = [&](Chunk ch, int span) { ch.span = span; chunks.push_back(ch); };
         if (pair) {
-            // one span; its K commands and V commands in the chosen order
+            // one span; its commands layer by layer, K's and V's in the chosen order
             const int si = emit_span(units[0][0].span);
-            const std::vector<Chunk> &ck = units[0][0].chunks, &cv = units[1][0].chunks;
+            std::vector<Chunk> &ck = units[0][0].chunks, &cv = units[1][0].chunks;
             if (order == KV_ORDER_INTRA) {
                 for (size_t i = 0; i < std::max(ck.size(), cv.size()); ++i) {
                     if (i < ck.size()) emit_chunk(ck[i], si);
                     if (i < cv.size()) emit_chunk(cv[i], si);
                 }
             } else {
-                for (const Chunk &c : ck) emit_chunk(c, si);
-                for (const Chunk &c : cv) emit_chunk(c, si);
+                // tensor-id order: K of a layer, then its V, then the next layer
+                std::vector<Chunk> all(ck);
+                all.insert(all.end(), cv.begin(), cv.end());
+                std::stable_sort(all.begin(), all.end(), [](const Chunk &a, const Chunk &b) {
+                    return a.layer != b.layer ? a.layer < b.layer : a.kind < b.kind;
+                });
+                for (const Chunk &c : all) emit_chunk(c, si);
             }
         } else if (order == KV_ORDER_INTRA) {
             for (size_t i = 0; i < std::max(units[0].size(), units[1].size()); ++i)
@@ -384,6 +406,7 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
                 }
         }
         if (!spans.empty()) spans.back().last_of_layer = true;
+        l += group;
     }
     // last chunk command of each path group (for the per-group throughput figures)
     long long *group_last = out->group_last;
@@ -474,13 +497,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     }
     const bool d2h_big = cmd_bytes >= (8ull << 20) || (cmd_bytes >= (2ull << 20) && depth >= 4);
     const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && !d2h_big);
-    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL;
+    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL || (h2d_mode == KV_COPY_AUTO && cmd_bytes <= (1ull << 20));
     const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
     const int order_direct = opts ? opts->order_direct : KV_ORDER_CROSS;
     if ((order_pc != KV_ORDER_CROSS && order_pc != KV_ORDER_INTRA) ||
         (order_direct != KV_ORDER_CROSS && order_direct != KV_ORDER_INTRA))
         return KV_EINVAL;
-    if (ns == 0) ns = offload_dir && d2h_kernel ? 3 : 4;
+    if (ns == 0) ns = offload_dir ? (d2h_kernel ? 3 : 4) : (h2d_kernel ? 2 : 4);
     ns = std::min(ns, depth);
     if (stats) std::memset(stats, 0, sizeof(*stats));
     if (layer_begin == layer_end) return KV_OK;
@@ -635,9 +658,10 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             return e != hipSuccess ? e : hipEventRecord(ev, st);
         }
         const size_t nvec = bytes / 16;
-        // 32 workgroups saturate the link (measured); a small grid also keeps the compute units whose
-        // store path backs up behind PCIe writes few, so the concurrent pack kernel is disturbed less
-        const unsigned blocks = (unsigned)std::min<size_t>(32, std::max<size_t>(1, nvec / (256 * 4)));
+        // 8 workgroups saturate the link and give the lowest per-command cost (measured over 2-32: a command of
+        // 512 KiB moves at 46 GB/s D2H / 52 GB/s H2D with 8, 45 / 42 with 32); a small grid also keeps the compute
+        // units whose store path backs up behind PCIe writes few, so the concurrent pack kernel is disturbed less
+        const unsigned blocks = (unsigned)std::min<size_t>(8, std::max<size_t>(1, nvec / (256 * 4)));
         hipExtLaunchKernelGGL(kv_chunk_copy_kernel, dim3(blocks), dim3(256), 0, st, nullptr, ev, 0, (const u32x4 *)src,
                               (u32x4 *)dst, nvec);
         return hipGetLastError();
@@ -648,24 +672,37 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     int ext_k_slot = -1;
 
     if (offload) {
+        // Pack of span i into its staging slot, on the kernel stream.  The kernel stream runs one span ahead of
+        // the transfers (four slots exist), so the link does not wait for a pack at a span boundary.
+        size_t n_packed = 0;
+        auto pack_span = [&](size_t si) -> int {
+            const Span &sp = spans[si];
+            const size_t slot = si % n_slots;
+            char *img = staging + slot * slot_bytes;
+            // the slot's previous copies must have left it before the kernel overwrites it
+            if (si >= n_slots)
+                for (int s = 0; s < ns; ++s)
+                    if (slot_used[slot] >> s & 1) KV_HIP(hipStreamWaitEvent(q->s_compute, q->ev_done[slot * kMaxCopyStreams + s], 0));
+            time_begin(KV_KERNEL_PACK);
+            const int rc = sp.n_layers > 1
+                               ? kv_offload_pack_layers(p, sp.layer, sp.layer + sp.n_layers, view, img, slot_bytes, q->s_compute)
+                               : kv_offload_pack(p, sp.layer, sp.kind, view, sp.seq, sp.tok0, sp.ntok, img, slot_bytes, q->s_compute);
+            time_end();
+            if (rc != KV_OK) return rc;
+            if (stats) { stats->kernel_launches[KV_KERNEL_PACK]++; stats->n_spans++; }
+            KV_HIP(hipEventRecord(q->ev_ready[slot], q->s_compute));
+            if (serialize) KV_HIP(hipStreamSynchronize(q->s_compute));
+            return KV_OK;
+        };
         for (size_t c = 0; c < N && err == KV_OK; ++c) {
             const Chunk &ch = chunks[c];
             const Span &sp = spans[ch.span];
             const size_t slot = (size_t)ch.span % n_slots;
             char *img = staging + slot * slot_bytes;
             if (ch.first) {
-                // the slot's previous copies must have left it before the kernel overwrites it
-                if ((size_t)ch.span >= n_slots)
-                    for (int s = 0; s < ns && err == KV_OK; ++s)
-                        if (slot_used[slot] >> s & 1) KV_HIP_SET(hipStreamWaitEvent(q->s_compute, q->ev_done[slot * kMaxCopyStreams + s], 0));
+                const size_t ahead = serialize ? 0 : 1;
+                while (err == KV_OK && n_packed < spans.size() && n_packed <= (size_t)ch.span + ahead) err = pack_span(n_packed++);
                 if (err != KV_OK) break;
-                time_begin(KV_KERNEL_PACK);
-                err = kv_offload_pack(p, sp.layer, sp.kind, view, sp.seq, sp.tok0, sp.ntok, img, slot_bytes, q->s_compute);
-                time_end();
-                if (err != KV_OK) break;
-                if (stats) { stats->kernel_launches[KV_KERNEL_PACK]++; stats->n_spans++; }
-                KV_HIP_BRK(hipEventRecord(q->ev_ready[slot], q->s_compute));
-                if (serialize) KV_HIP_BRK(hipStreamSynchronize(q->s_compute));
                 used = 0;
             }
             if ((err = entry_free(c)) != KV_OK || (err = transfer_slot(c)) != KV_OK) break;
@@ -749,18 +786,22 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 if (err != KV_OK) break;
                 if (!attn_from_extent) {
                     time_begin(KV_KERNEL_UNPACK);
-                    err = kv_reload_unpack(p, sp.layer, sp.kind, img, slot_bytes, view, sp.seq, sp.tok0, sp.ntok, q->s_compute);
+                    err = sp.n_layers > 1
+                              ? kv_reload_unpack_layers(p, sp.layer, sp.layer + sp.n_layers, img, slot_bytes, view, q->s_compute)
+                              : kv_reload_unpack(p, sp.layer, sp.kind, img, slot_bytes, view, sp.seq, sp.tok0, sp.ntok, q->s_compute);
                     time_end();
                     if (err != KV_OK) break;
                     if (stats) { stats->kernel_launches[KV_KERNEL_UNPACK]++; stats->n_spans++; }
                     KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_compute));
                     if (dir == KV_DIR_RELOAD_ATTN && sp.last_of_layer) {
-                        time_begin(KV_KERNEL_ATTN_PARTIAL);  // partial + combine bracketed together
-                        err = kv_decode_attn(p, view, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
-                                             attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
-                        time_end();
+                        for (int l = sp.layer; l < sp.layer + sp.n_layers && err == KV_OK; ++l) {
+                            time_begin(KV_KERNEL_ATTN_PARTIAL);  // partial + combine bracketed together
+                            err = kv_decode_attn(p, view, l, attn->q_layers[l], attn->out_layers[l], attn->out_dtype,
+                                                 attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
+                            time_end();
+                            if (err == KV_OK && stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
+                        }
                         if (err != KV_OK) break;
-                        if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
                     }
                 } else {
                     // Attention straight from the staged extent images: extent order (S, B*H, D) is the
@@ -769,10 +810,6 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                     if (sp.kind != KV_V) ext_k_img = img;  // KV_K or KV_KV span
                     if (sp.kind == KV_K) { ext_k_slot = (int)slot; }
                     if (sp.last_of_layer) {
-                        char *vimg = sp.kind == KV_KV ? img + image : img;
-                        for (int l = 0; l < view->n_layers; ++l) { ext_k[l] = nullptr; ext_v[l] = nullptr; }
-                        ext_k[sp.layer] = ext_k_img;
-                        ext_v[sp.layer] = vimg;
                         kv_view_t ev = *view;
                         ev.layout = KV_LAYOUT_BHSD;
                         ev.k_layers = ext_k.data();
@@ -790,12 +827,18 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                             ev.seq_off_host = q->seq_off_host.data();
                             ev.seq_off_dev = (const int64_t *)q->seq_off_dev;
                         }
-                        time_begin(KV_KERNEL_ATTN_PARTIAL);
-                        err = kv_decode_attn(p, &ev, sp.layer, attn->q_layers[sp.layer], attn->out_layers[sp.layer],
-                                             attn->out_dtype, attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
-                        time_end();
+                        for (int l = sp.layer; l < sp.layer + sp.n_layers && err == KV_OK; ++l) {
+                            // a span of several layers holds K and V of layer l at images 2(l - first), 2(l - first) + 1
+                            const uint64_t j = (uint64_t)(l - sp.layer);
+                            ext_k[l] = sp.kind == KV_KV ? img + 2 * j * image : ext_k_img;
+                            ext_v[l] = sp.kind == KV_KV ? img + (2 * j + 1) * image : img;
+                            time_begin(KV_KERNEL_ATTN_PARTIAL);
+                            err = kv_decode_attn(p, &ev, l, attn->q_layers[l], attn->out_layers[l], attn->out_dtype,
+                                                 attn->n_splits, q->attn_ws, q->attn_ws_bytes, q->s_compute);
+                            time_end();
+                            if (err == KV_OK && stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
+                        }
                         if (err != KV_OK) break;
-                        if (stats) { stats->kernel_launches[KV_KERNEL_ATTN_PARTIAL]++; stats->kernel_launches[KV_KERNEL_ATTN_COMBINE]++; }
                         KV_HIP_BRK(hipEventRecord(q->ev_free[slot], q->s_compute));
                         if (sp.kind == KV_V && ext_k_slot >= 0) KV_HIP_BRK(hipEventRecord(q->ev_free[ext_k_slot], q->s_compute));
                     }

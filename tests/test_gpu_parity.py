@@ -115,6 +115,41 @@ def test_pack_unpack_both_tensors_in_one_launch(case):
 
 
 # ------------------------------------------------------------------------------------------ unpack
+def test_pack_unpack_several_layers_in_one_call(case):
+    """kv_offload_pack_layers / kv_reload_unpack_layers: the images of K and V of a run of layers, back to back in
+    tensor-id order, equal the single-tensor images; the inverse restores every layer of the run and no other."""
+    r, L = case.ref, case.cfg.n_layers
+    image = r.n_blocks_tensor * r.lba_size
+    for lb, le in ((0, L), (L - 1, L), (1, 1)):
+        n = le - lb
+        buf, dst = _guarded(2 * n * image)
+        if n == 0:
+            dst = buf                                      # an empty run writes nothing anywhere
+        kv.kv_offload_pack_layers(case.plan, lb, le, case.view, dst)
+        torch.cuda.synchronize()
+        got = dst.cpu().numpy()
+        for l in range(lb, le):
+            for kind in (0, 1):
+                j = (l - lb) * 2 + kind
+                assert np.array_equal(got[j * image:(j + 1) * image], case.expected_extent(l, kind)), (lb, le, l, kind)
+        assert _guards_intact(buf, 2 * n * image) and (n > 0 or (buf.cpu().numpy() == CANARY).all())
+        k_new, v_new = case.blank_like_source()
+        kv.kv_reload_unpack_layers(case.plan, lb, le, dst, case.make_view(k_new, v_new))
+        torch.cuda.synchronize()
+        _check_restored(case, k_new, v_new, range(lb, le))
+        for l in set(range(L)) - set(range(lb, le)):       # layers outside the run keep their fill
+            assert (bits(k_new[l]) == 0x7E7E).all() and (bits(v_new[l]) == 0x7E7E).all()
+    small = torch.empty(2 * L * image - 16, dtype=torch.uint8, device="cuda")
+    for f, args in ((kv.kv_offload_pack_layers, (case.plan, 0, L, case.view, small)),
+                    (kv.kv_reload_unpack_layers, (case.plan, 0, L, small, case.view))):
+        with pytest.raises(kv.KVError) as e:
+            f(*args)
+        assert e.value.code == kv.KV_ENOSPC
+    with pytest.raises(kv.KVError) as e:
+        kv.kv_offload_pack_layers(case.plan, 0, L + 1, case.view, small)
+    assert e.value.code == kv.KV_ERANGE
+
+
 def _check_restored(case, k_new, v_new, layers, fill=0x7E7E):
     cfg = case.cfg
     for layer in layers:
