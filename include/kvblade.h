@@ -324,6 +324,19 @@ int kv_decode_attn(const kv_plan_t *plan, const kv_view_t *kv, int layer, const 
 size_t kv_decode_attn_workspace(const kv_plan_t *plan, int n_splits, int max_len);
 
 /*
+ * kv_decode_attn_splits -- the token splits kv_decode_attn makes for sequences of the given lengths (host [B]) and
+ * the given n_splits argument (0 = choose): *n_splits_out = the split count the partials are laid out for (the
+ * workspace holds batch * n_q_heads * that * (head_dim + 2) floats); first (host [B+1], nullable) = index of each
+ * sequence's first split among the splits that hold tokens, first[B] = their number (workgroups launched per
+ * query-head group); tokens (host [B], nullable) = token rows per split of each sequence.  Host arithmetic only.
+ * A uniform batch, or a given n_splits, takes one split length for all sequences; a ragged batch of up to 64
+ * sequences with n_splits = 0 gets per-sequence split lengths such that every workgroup reads about the same
+ * number of tokens (about one workgroup per compute unit in all).
+ */
+int kv_decode_attn_splits(const kv_plan_t *plan, const int32_t *seq_lens_host, int n_splits, int *n_splits_out,
+                          int *first, int *tokens);
+
+/*
  * kv_decode_attn_static -- kv_decode_attn for callers that cannot allocate device memory (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, result and errors,
  * but no workspace argument.  The split partials live in an array of KV_ATTN_SCRATCH_BYTES that is part of

@@ -39,6 +39,7 @@ EXPORTS = [
     "kv_decode_attn_workspace", "kv_pipeline_run", "kv_last_hip_error", "kv_strerror", "kv_abi_version",
     "kv_append_tokens", "kv_budget", "kv_plan_trim", "kv_adapt_init", "kv_adapt_order", "kv_adapt_update",
     "kv_abi_sizeof", "kv_budget_sample", "kv_decode_attn_static", "kv_offload_pack_layers", "kv_reload_unpack_layers",
+    "kv_decode_attn_splits",
 ]
 
 
@@ -139,6 +140,7 @@ def lib() -> C.CDLL:
         L.kv_reload_unpack_layers.argtypes = [vp, i, i, vp, C.c_size_t, C.POINTER(kv_view_t), vp]
         L.kv_decode_attn.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp, C.c_size_t, vp]
         L.kv_decode_attn_static.argtypes = [vp, C.POINTER(kv_view_t), i, vp, vp, i, i, vp]
+        L.kv_decode_attn_splits.argtypes = [vp, C.POINTER(C.c_int32), i, C.POINTER(i), C.POINTER(i), C.POINTER(i)]
         L.kv_decode_attn_workspace.argtypes = [vp, i, i]
         L.kv_decode_attn_workspace.restype = C.c_size_t
         L.kv_pipeline_run.argtypes = [vp, i, i, i, C.POINTER(kv_view_t), vp, C.c_size_t, vp, C.c_size_t, i, i,
@@ -358,6 +360,17 @@ def kv_reload_unpack_layers(plan: Plan, layer_begin: int, layer_end: int, src, d
     _check(lib().kv_reload_unpack_layers(plan.handle, layer_begin, layer_end, src.data_ptr(),
                                          src.numel() * src.element_size(), dst.ref(), _caller_stream(stream)),
            "kv_reload_unpack_layers")
+
+
+def kv_decode_attn_splits(plan: Plan, seq_lens: Sequence[int], n_splits: int = 0):
+    """(split count of the partial layout, first[B+1], tokens[B]) as kv_decode_attn would split these lengths."""
+    B = len(seq_lens)
+    lens = (C.c_int32 * B)(*[int(x) for x in seq_lens])
+    ns = C.c_int()
+    first = (C.c_int * (B + 1))()
+    tokens = (C.c_int * B)()
+    _check(lib().kv_decode_attn_splits(plan.handle, lens, n_splits, C.byref(ns), first, tokens), "kv_decode_attn_splits")
+    return int(ns.value), list(first), list(tokens)
 
 
 def kv_decode_attn_workspace(plan: Plan, n_splits: int, max_len: int) -> int:

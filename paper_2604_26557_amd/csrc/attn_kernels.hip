@@ -1,8 +1,11 @@
 // Split-K decode attention over resident KV (Sec. II-A: the query's similarity with the keys weights
 // the values):  out[b,hq,:] = softmax_j(q[b,hq,:].K[b,h,j,:] / sqrt(D)) V[b,h,j,:],  h = hq / G.
 //
-// Partial kernel, grid (split, query-head group, b), 4 wavefronts per workgroup, each walking 16-token
-// tiles of its split.
+// Partial kernel: one workgroup of 8 wavefronts per (sequence, query-head group, token split), about one
+// workgroup per compute unit.  A step is a tile of 16 tokens (two tiles when D = 64); the steps of a split
+// are handed out to the wavefronts on demand through a counter in LDS, so a wavefront whose loads come back
+// late takes fewer steps and all eight reach the merge together (with a fixed round-robin the slowest
+// wavefront, and the second workgroup of a compute unit, finished 2-4 us after the median).
 //  * q K^T on the matrix cores: one v_mfma_f32_16x16x32 per 32-wide slice of D with the K tile as the
 //    16 x 32 A operand (lane = token row, 16 contiguous bytes of it) and the query heads of the group,
 //    repeated across the 16 columns, as the B operand.  A 16-byte global load is exactly one operand
@@ -12,8 +15,9 @@
 //    in fp32; probabilities and rescale factors reach the other heads' lanes by quad broadcasts (DPP).
 //  * P V stays on the vector ALU: the 16 lanes of a row group hold the V rows of their own 4 tokens
 //    (16 bytes per lane), so acc[g][d] += p[g][token] * V[token][d] needs no transpose of V.
-// Row groups, then wavefronts, are merged at the end and one fp32 partial per (b, hq, split) is
-// written; the combine kernel merges the splits.  HBM-bound (G flop per byte).
+//  * K and V are read once and never again: the loads are nontemporal.
+// The 32 (wavefront, row group) softmax states of a head are merged through LDS and one fp32 partial per
+// (b, hq, split) is written; the combine kernel merges the splits.  HBM-bound (G flop per byte).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -32,11 +36,19 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kTile = 16;             // tokens per MFMA tile
-constexpr int tiles_per_iter(int D) { return D >= 256 ? 1 : (D == 128 ? 2 : 4); }
+constexpr int tiles_per_step(int D) { return D >= 128 ? 1 : 2; }  // 8 KiB of K and V in flight per wavefront
 constexpr float kEmptyMax = -1.0e30f; // running maximum of a row group that has seen no token
+constexpr int kMaxTableSeqs = 64;     // ragged batches up to this size get per-sequence split counts
+
+// Ragged batch: sequence b owns work items [first[b], first[b+1]) of the grid's x dimension, each of
+// tokens[b] token rows (the last one shorter).
+struct SplitTable {
+    int first[kMaxTableSeqs + 1];
+    int tokens[kMaxTableSeqs];
+};
 
 struct AttnParams {
     const u32x4 *K, *V;    // attention-side buffers of the layer
@@ -50,7 +62,7 @@ struct AttnParams {
     const int *table;      // paged layout
     int max_blocks, bt, bt_shift, n_pool;
     int H, Hq, G, B;
-    int compact;           // 1: blockIdx.x counts only the splits that hold tokens, sequence after sequence
+    int use_table;         // 1: blockIdx.x is a work item of the split table; 0: grid (split, head group, sequence)
     int n_splits, split_tokens;
     int max_len;           // host-checked bound on every sequence length
     float scale_log2e;     // log2(e) / sqrt(D)
@@ -73,11 +85,39 @@ __device__ __forceinline__ void unpack8(u32x4 v, float f[8])
     }
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float rdlane(float x, int l)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
+}
+// Wavefront-wide maximum / sum over all 64 lanes, result uniform: four DPP steps inside each row of 16 lanes
+// (vector-ALU speed, no trip through the LDS crossbar), then the four row results through scalar registers.
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = fmaxf(x, dpp_mov<0xB1>(x));   // quad_perm [1,0,3,2]
+    x = fmaxf(x, dpp_mov<0x4E>(x));   // quad_perm [2,3,0,1]
+    x = fmaxf(x, dpp_mov<0x141>(x));  // row_half_mirror
+    x = fmaxf(x, dpp_mov<0x140>(x));  // row_mirror
+    return fmaxf(fmaxf(rdlane(x, 0), rdlane(x, 16)), fmaxf(rdlane(x, 32), rdlane(x, 48)));
+}
+__device__ __forceinline__ float wave_sum(float x)
+{
+    x += dpp_mov<0xB1>(x);
+    x += dpp_mov<0x4E>(x);
+    x += dpp_mov<0x141>(x);
+    x += dpp_mov<0x140>(x);
+    return (rdlane(x, 0) + rdlane(x, 16)) + (rdlane(x, 32) + rdlane(x, 48));
+}
+
 // Value of quad lane Q (0..3) in every lane of the quad.
 template <int Q>
 __device__ __forceinline__ float quad_bcast(float x)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), Q * 0x55, 0xf, 0xf, false));
+    return dpp_mov<Q * 0x55>(x);
 }
 template <int GT>
 __device__ __forceinline__ float head_bcast(float x, int g)
@@ -91,7 +131,7 @@ __device__ __forceinline__ float head_bcast(float x, int g)
     }
 }
 
-// Merge the running softmax state of another lane / wavefront into this one.
+// Merge the running softmax state of another lane into this one.
 template <int N>
 __device__ __forceinline__ void merge(float &m, float &l, float acc[N], float m2, float l2, const float acc2[N])
 {
@@ -111,8 +151,19 @@ __device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+// Sequence that owns work item `item` of the split table: the last b with first[b] <= item (uniform, scalar).
+__device__ __forceinline__ int table_owner(const SplitTable &t, int B, int item)
+{
+    int lo = 0, hi = B;  // first[lo] <= item < first[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (t.first[mid] <= item) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 template <int D, int GT, bool BF16, bool PAGED>
-__global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
+__global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p, SplitTable tab)
 {
     constexpr int NJ = D / 32;               // MFMA slices along D
     constexpr int DV = D / 8;                // 16-byte vectors per row
@@ -121,26 +172,18 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
     constexpr int NV = DV / LPRV;            // vectors per lane per V row (1, or 2 when D = 256)
     constexpr int NU = 4 / TPL;              // V loads (per vector) for the 4 tokens of a row group
     constexpr int AE = 8 * NV;               // accumulator elements per head per lane
-    constexpr int TI = tiles_per_iter(D);    // tiles whose loads are issued together (16 KiB in flight per wavefront)
+    constexpr int TI = tiles_per_step(D);    // tiles of one step
+    constexpr int kStepTok = kTile * TI;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int split = blockIdx.x, b = blockIdx.z;
-    if (p.compact) {
-        // Ragged batch (B <= 64): no workgroup is launched for a split without tokens.  Lane s holds the split
-        // count of sequence s; an inclusive scan over the wavefront and a ballot find the sequence that owns
-        // work item blockIdx.x (every wavefront does the same).
-        int nb = 0;
-        if (lane < p.B) nb = (min(p.seq_lens[lane], p.max_len) + p.split_tokens - 1) / p.split_tokens;
-        int incl = nb;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-        }
-        const unsigned long long owners = __ballot((int)blockIdx.x < incl);
-        if (owners == 0) return;  // not reached: the grid has exactly the sum of the split counts
-        b = __ffsll((long long)owners) - 1;
-        split = (int)blockIdx.x - __shfl(incl - nb, b);
+    int split = blockIdx.x, b = blockIdx.z, split_tokens = p.split_tokens;
+    if (p.use_table) {
+        // Ragged batch: the grid's x dimension counts only splits that hold tokens, sequence after sequence,
+        // each sequence cut into its own number of equal splits (sized on the host so that every workgroup
+        // gets about the same number of tokens).
+        b = table_owner(tab, p.B, (int)blockIdx.x);
+        split = (int)blockIdx.x - tab.first[b];
+        split_tokens = tab.tokens[b];
     }
     const int hq0 = blockIdx.y * GT;
     const int h = hq0 / p.G;
@@ -150,8 +193,8 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
     const int lr = n % LPRV, half = n / LPRV;
 
     const int len = p.len_uniform >= 0 ? p.len_uniform : min(p.seq_lens[b], p.max_len);
-    const int t_begin = min(len, split * p.split_tokens);
-    const int t_end = min(len, t_begin + p.split_tokens);
+    const int t_begin = min(len, split * split_tokens);
+    const int t_end = min(len, t_begin + split_tokens);
 
     // B operand: column n carries query head n mod GT; this lane holds elements 32j + 8tg .. +7 of it.
     u32x4 qv[NJ];
@@ -178,8 +221,8 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
         }
         return head_off + (long long)row * p.ss;
     };
-    // Paged layout: the block ids of one iteration's rows -- this lane's K row and the 4 tokens of its row
-    // group, per tile -- are fetched one iteration ahead, so that the table lookup is off the load chain.
+    // Paged layout: the block ids of one step's rows -- this lane's K row and the 4 tokens of its row group,
+    // per tile -- are fetched one step ahead, so that the table lookup is off the load chain.
     struct Ids { int k[TI]; int t[TI][4]; };
     auto fetch_ids = [&](int Tw, Ids &ids) {
 #pragma unroll
@@ -193,12 +236,21 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
             }
         }
     };
-    Ids ids{};
-    const int Tw0 = t_begin + kTile * TI * wave;
-    if (PAGED && Tw0 < t_end) fetch_ids(Tw0, ids);
 
-    for (int Tw = Tw0; Tw < t_end; Tw += kTile * TI * kWaves) {
-        // ---- loads of TI adjacent tiles: K tile in A-operand order, V rows of this row group's tokens
+    // Steps are handed out in order, on demand.  A wavefront always knows its current and its next step; the
+    // one after that is claimed (one LDS atomic by lane 0) right after the current step's loads are issued,
+    // so neither the atomic nor, for the paged layout, the block-table lookup sits on the load chain.
+    __shared__ int sh_next;
+    const int n_steps = (t_end - t_begin + kStepTok - 1) / kStepTok;
+    if (threadIdx.x == 0) sh_next = 2 * kWaves;   // steps 0 .. 2*kWaves-1 are preassigned: w and w + kWaves to wavefront w
+    __syncthreads();
+    int s_cur = wave, s_nxt = wave + kWaves;
+    Ids ids{};
+    if (PAGED && s_cur < n_steps) fetch_ids(t_begin + s_cur * kStepTok, ids);
+
+    while (s_cur < n_steps) {
+        const int Tw = t_begin + s_cur * kStepTok;
+        // ---- loads of the step's tiles: K tile in A-operand order, V rows of this row group's tokens
         u32x4 kvec[TI][NJ];
         u32x4 vvec[TI][NU][NV];
         bool tok_ok[TI][4];
@@ -209,7 +261,7 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
             const int krow = (T0 + n < t_end) ? T0 + n : t_begin;  // rows past the end re-read a valid row; masked below
             const long long kb = row_base(krow, PAGED ? ids.k[ti] : 0, k_ok);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) kvec[ti][j] = p.K[kb + 4 * j + tg];
+            for (int j = 0; j < NJ; ++j) kvec[ti][j] = __builtin_nontemporal_load(p.K + kb + 4 * j + tg);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 // a token whose block id is outside the pool is not attended; every lane of the row group
@@ -225,13 +277,13 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
                 const int blk = !PAGED ? 0 : (TPL == 1 ? ids.t[ti][u] : (half ? ids.t[ti][(2 * u + 1) & 3] : ids.t[ti][(2 * u) & 3]));
                 const long long vb = row_base(tok < t_end ? tok : t_begin, blk, ok);
 #pragma unroll
-                for (int w = 0; w < NV; ++w) vvec[ti][u][w] = p.V[vb + lr + w * LPRV];
+                for (int w = 0; w < NV; ++w) vvec[ti][u][w] = __builtin_nontemporal_load(p.V + vb + lr + w * LPRV);
             }
         }
-        if (PAGED) {
-            const int next = Tw + kTile * TI * kWaves;
-            if (next < t_end) fetch_ids(next, ids);
-        }
+        int s_new = 0;
+        if (lane == 0) s_new = atomicAdd(&sh_next, 1);
+        s_new = __builtin_amdgcn_readfirstlane(s_new);
+        if (PAGED && s_nxt < n_steps) fetch_ids(t_begin + s_nxt * kStepTok, ids);
 
 #pragma unroll
         for (int ti = 0; ti < TI; ++ti) {
@@ -275,81 +327,74 @@ __global__ void __launch_bounds__(kThreads) kv_attn_partial_kernel(AttnParams p)
                 }
             }
         }
+        s_cur = s_nxt;
+        s_nxt = s_new;
     }
 
-    // ---- merge: every (wavefront, row group) is one softmax state (m, l, acc[D]) per head.  The states go
-    // to LDS as they are (for D = 256 row-group pairs are first merged by one shuffle round, to halve the
-    // LDS footprint), their weights exp2(m - M) are computed once per (state, head), and the workgroup then
-    // forms the weighted sums: far fewer instructions than merging in registers through shuffles.
-    constexpr int SR = D == 256 ? 1 : 0;       // shuffle rounds before LDS
+    // ---- merge: every (wavefront, row group) is one softmax state (m, l, acc[D]) per head.  The states go to
+    // LDS as they are (when four heads of 256 columns would not fit, row-group pairs are first merged by one
+    // shuffle round).  After one barrier a wavefront that forms 64 outputs of head g computes the weights
+    // exp2(m - M) of that head's states itself (lane = state, two DPP reductions) and takes them from the lanes
+    // by readlane while it sums the weighted states.
+    constexpr int SR = GT * D > 512 ? 1 : 0;   // shuffle rounds before LDS
     constexpr int NS = kWaves * (4 >> SR);     // states per head in LDS
-    float mg[GT], lg[GT];
-#pragma unroll
-    for (int g = 0; g < GT; ++g) {
-        mg[g] = head_bcast<GT>(m_own, g);
-        lg[g] = head_bcast<GT>(l_own, g);
-    }
+    static_assert(NS <= 64, "one lane per state");
+    float mg = m_own, lg = l_own;
     if (TPL == 2) {  // the two halves of a row group share (m, l) and hold different tokens of the same d
 #pragma unroll
         for (int g = 0; g < GT; ++g)
 #pragma unroll
             for (int e = 0; e < AE; ++e) acc[g][e] += __shfl_xor(acc[g][e], 8);
     }
-#pragma unroll
-    for (int r = 0; r < SR; ++r) {
-        const int off = 16 << r;
+    if (SR == 1) {   // lane (n, tg) and lane (n, tg ^ 1) hold states of the same head n mod GT
+        float mh[GT], lh[GT];
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            const float m2 = __shfl_xor(mg[g], off), l2 = __shfl_xor(lg[g], off);
+            mh[g] = head_bcast<GT>(m_own, g);
+            lh[g] = head_bcast<GT>(l_own, g);
+            const float m2 = __shfl_xor(mh[g], 16), l2 = __shfl_xor(lh[g], 16);
             float a2[AE];
 #pragma unroll
-            for (int e = 0; e < AE; ++e) a2[e] = __shfl_xor(acc[g][e], off);
-            merge<AE>(mg[g], lg[g], acc[g], m2, l2, a2);
+            for (int e = 0; e < AE; ++e) a2[e] = __shfl_xor(acc[g][e], 16);
+            merge<AE>(mh[g], lh[g], acc[g], m2, l2, a2);
         }
+        // back to "lane n holds the state of head n mod GT"
+        mg = mh[0]; lg = lh[0];
+#pragma unroll
+        for (int g = 1; g < GT; ++g)
+            if (g_own == g) { mg = mh[g]; lg = lh[g]; }
     }
 
     __shared__ __attribute__((aligned(16))) float sh_acc[NS][GT][D];
-    __shared__ float sh_ml[NS][GT][2];
-    __shared__ float sh_w[NS][GT];
-    __shared__ float sh_ML[GT][2];
+    __shared__ f32x2 sh_ml[GT][NS];
     const int state = wave * (4 >> SR) + (tg >> SR);
     if ((tg & ((1 << SR) - 1)) == 0 && half == 0) {
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
 #pragma unroll
             for (int w = 0; w < NV; ++w) {
-                float *dst = &sh_acc[state][g][(lr + w * LPRV) * 8];
-                *(f32x4 *)dst = f32x4{acc[g][w * 8 + 0], acc[g][w * 8 + 1], acc[g][w * 8 + 2], acc[g][w * 8 + 3]};
-                *(f32x4 *)(dst + 4) = f32x4{acc[g][w * 8 + 4], acc[g][w * 8 + 5], acc[g][w * 8 + 6], acc[g][w * 8 + 7]};
+                // a wavefront's 16-byte stores are contiguous: position ((2w + e4) * LPRV + lr) * 4 + k of a state
+                // row holds column d = (lr + w * LPRV) * 8 + 4 * e4 + k
+                *(f32x4 *)&sh_acc[state][g][((2 * w) * LPRV + lr) * 4] = f32x4{acc[g][w * 8 + 0], acc[g][w * 8 + 1], acc[g][w * 8 + 2], acc[g][w * 8 + 3]};
+                *(f32x4 *)&sh_acc[state][g][((2 * w + 1) * LPRV + lr) * 4] = f32x4{acc[g][w * 8 + 4], acc[g][w * 8 + 5], acc[g][w * 8 + 6], acc[g][w * 8 + 7]};
             }
-            if (n == 0) { sh_ml[state][g][0] = mg[g]; sh_ml[state][g][1] = lg[g]; }
         }
+        if (n < GT) sh_ml[n][state] = f32x2{mg, lg};   // lane n < GT holds the state of head n
     }
     __syncthreads();
-    if (threadIdx.x < GT) {  // one thread per head: maximum, weights, denominator
-        const int g = threadIdx.x;
-        float M = sh_ml[0][g][0];
-#pragma unroll
-        for (int st = 1; st < NS; ++st) M = fmaxf(M, sh_ml[st][g][0]);
-        float L = 0.f;
-#pragma unroll
-        for (int st = 0; st < NS; ++st) {
-            const float a = exp2f(sh_ml[st][g][0] - M);
-            sh_w[st][g] = a;
-            L += sh_ml[st][g][1] * a;
-        }
-        sh_ML[g][0] = M;
-        sh_ML[g][1] = L;
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < GT * D; idx += kThreads) {
-        const int g = idx / D, d = idx - g * D;
+    for (int base = wave * 64; base < GT * D; base += kThreads) {   // 64 consecutive positions of one head per wavefront
+        const int g = base / D, pos = base - g * D + lane;
+        const int d = (((pos >> 2) % LPRV) + ((pos >> 2) / LPRV / 2) * LPRV) * 8 + (((pos >> 2) / LPRV) & 1) * 4 + (pos & 3);
+        const f32x2 ml = lane < NS ? sh_ml[g][lane] : f32x2{kEmptyMax, 0.f};
+        const float M = wave_max(ml[0]);
+        const float wgt = exp2f(ml[0] - M);
+        const float L = wave_sum(ml[1] * wgt);
         float A = 0.f;
 #pragma unroll
-        for (int st = 0; st < NS; ++st) A = fmaf(sh_acc[st][g][d], sh_w[st][g], A);
+        for (int st = 0; st < NS; ++st) A = fmaf(sh_acc[st][g][pos], rdlane(wgt, st), A);
         const long long o = ((long long)b * p.Hq + hq0 + g) * p.n_splits + split;
         p.part_acc[o * D + d] = A;
-        if (d == 0) { p.part_ml[o * 2] = sh_ML[g][0]; p.part_ml[o * 2 + 1] = sh_ML[g][1]; }
+        if (pos == 0) *(f32x2 *)&p.part_ml[o * 2] = f32x2{M, L};
     }
 }
 
@@ -361,92 +406,84 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
     return (unsigned short)(u >> 16);
 }
 
-// out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup of 256 threads per (hq, b, 32 output columns): threads are
-// (column, split group), eight groups, group k summing splits k, k+8, ...  The loads of a thread's first
-// kCombinePrefetch partial rows do not depend on the split weights, so they are issued first and the two
-// memory latencies (weights' inputs, partial rows) overlap.  The weights exp2(m_s - M) go to LDS.
+// out_mode: 0 fp32, 1 fp16, 2 bf16.  One workgroup of 256 threads per (hq, b): threads are (column, split group);
+// a wavefront covers 64 columns of one split group, so the split index is uniform over the wavefront.  Every
+// wavefront forms the split weights exp2(m_s - M) itself (lane = split, two DPP reductions; splits beyond 64 in
+// further rounds) and takes them from the lanes by readlane.  The loads of the (m, l) pairs and of a thread's
+// first 16 partial rows do not depend on each other and are issued together, so the kernel is one memory
+// latency long; the split groups are added through LDS.
 constexpr int kCombineThreads = 256;
-constexpr int kCombineCols = 32;
-constexpr int kCombineGroups = kCombineThreads / kCombineCols;
-constexpr int kCombinePrefetch = 8;
 constexpr int kMaxSplits = 1024;
 
+template <int D>
 __global__ void __launch_bounds__(kCombineThreads)
 kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-                       void *__restrict__ out, int Hq, int D, int n_splits_alloc, int out_mode,
-                       const int *__restrict__ seq_lens, int len_uniform, int max_len, int split_tokens)
+                       void *__restrict__ out, int Hq, int n_splits_alloc, int out_mode,
+                       const int *__restrict__ seq_lens, int len_uniform, int max_len, int split_tokens,
+                       int use_table, SplitTable tab)
 {
-    __shared__ float w[kMaxSplits];
-    __shared__ float colsum[kCombineThreads / 64][kCombineCols];
-    const int hq = blockIdx.x, b = blockIdx.y, d = blockIdx.z * kCombineCols + (threadIdx.x & (kCombineCols - 1));
-    const int tid = threadIdx.x, lane = tid & 63, grp = tid / kCombineCols;
+    constexpr int CW = D / 64;                       // wavefronts that cover the columns once
+    constexpr int NG = (kCombineThreads / 64) / CW;  // split groups (D = 256: 1, 128: 2, 64: 4)
+    constexpr int kRows = 16;                        // partial rows a thread loads per round
+    const int hq = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = __builtin_amdgcn_readfirstlane(wave / CW), d = (wave % CW) * 64 + lane;
     const long long o = ((long long)b * Hq + hq) * n_splits_alloc;
     // only the splits that hold tokens of this sequence were written (and matter)
-    const int len = len_uniform >= 0 ? len_uniform : min(seq_lens[b], max_len);
-    const int n_splits = min(n_splits_alloc, (len + split_tokens - 1) / split_tokens);
+    int n_splits;
+    if (use_table) {
+        n_splits = tab.first[b + 1] - tab.first[b];
+    } else {
+        const int len = len_uniform >= 0 ? len_uniform : min(seq_lens[b], max_len);
+        n_splits = min(n_splits_alloc, (len + split_tokens - 1) / split_tokens);
+    }
 
-    float pre[kCombinePrefetch];
+    f32x2 ml0 = f32x2{kEmptyMax, 0.f};
+    if (lane < n_splits) ml0 = *(const f32x2 *)&part_ml[(o + lane) * 2];
+    float pre[kRows];
 #pragma unroll
-    for (int i = 0; i < kCombinePrefetch; ++i) {
-        const int s = grp + i * kCombineGroups;
+    for (int i = 0; i < kRows; ++i) {                // first round's rows: independent of the weights
+        const int s = grp + i * NG;
         pre[i] = s < n_splits ? part_acc[(o + s) * D + d] : 0.f;
     }
+    // global maximum over all splits (the pairs just loaded; a tail loop when there are more than 64)
+    float M = ml0[0];
+    for (int s = 64 + lane; s < n_splits; s += 64) M = fmaxf(M, part_ml[(o + s) * 2]);
+    M = wave_max(M);
 
-    // Wavefront 0 alone forms the maximum, the weights and the denominator: one load of its lanes' (m, l)
-    // pairs (two per lane cover 128 splits; a rare tail loop takes the rest), two shuffle reductions.
-    float L = 0.f;
-    if (tid < 64) {
-        float m2[2], l2[2];
+    float A = 0.f, L = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += 64) {      // rounds of 64 splits: lane = split
+        f32x2 ml = ml0;
+        if (s0 > 0) {
+            ml = f32x2{kEmptyMax, 0.f};
+            if (s0 + lane < n_splits) ml = *(const f32x2 *)&part_ml[(o + s0 + lane) * 2];
+        }
+        const float wgt = exp2f(ml[0] - M);
+        L = fmaf(ml[1], wgt, L);
+        for (int r0 = 0; r0 < 64 && s0 + r0 < n_splits; r0 += kRows * NG) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int s = lane + 64 * i;
-            m2[i] = kEmptyMax;
-            l2[i] = 0.f;
-            if (s < n_splits) {
-                const f32x2 v = *(const f32x2 *)&part_ml[(o + s) * 2];
-                m2[i] = v[0];
-                l2[i] = v[1];
+            for (int i = 0; i < kRows; ++i) {
+                const int sl = r0 + grp + i * NG;     // uniform over the wavefront
+                const int s = s0 + sl;
+                if (sl < 64 && s < n_splits) {
+                    const float v = (s0 == 0 && r0 == 0) ? pre[i] : part_acc[(o + s) * D + d];
+                    A = fmaf(v, rdlane(wgt, sl), A);
+                }
             }
         }
-        float mx = fmaxf(m2[0], m2[1]);
-        for (int s = lane + 128; s < n_splits; s += 64) mx = fmaxf(mx, part_ml[(o + s) * 2]);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-        const float M = mx;
-        float lsum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int s = lane + 64 * i;
-            const float a = exp2f(m2[i] - M);
-            if (s < n_splits) w[s] = a;
-            lsum += l2[i] * a;
-        }
-        for (int s = lane + 128; s < n_splits; s += 64) {
-            const float a = exp2f(part_ml[(o + s) * 2] - M);
-            w[s] = a;
-            lsum += part_ml[(o + s) * 2 + 1] * a;
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off);
-        L = lsum;
     }
-    __syncthreads();
+    L = wave_sum(L);
 
-    float A = 0.f;
+    __shared__ float colsum[NG][D];
+    if (NG > 1) {
+        colsum[grp][d] = A;
+        __syncthreads();
+        if (grp == 0) {
 #pragma unroll
-    for (int i = 0; i < kCombinePrefetch; ++i) {
-        const int s = grp + i * kCombineGroups;
-        if (s < n_splits) A = fmaf(pre[i], w[s], A);
+            for (int k = 1; k < NG; ++k) A += colsum[k][d];
+        }
     }
-#pragma unroll 4
-    for (int s = grp + kCombinePrefetch * kCombineGroups; s < n_splits; s += kCombineGroups)
-        A = fmaf(part_acc[(o + s) * D + d], w[s], A);
-    A += __shfl_xor(A, 32);  // the two split groups of a wavefront
-    if (lane < kCombineCols) colsum[tid >> 6][lane] = A;
-    __syncthreads();
-    if (tid < kCombineCols) {
-#pragma unroll
-        for (int k = 1; k < kCombineThreads / 64; ++k) A += colsum[k][tid];
+    if (grp == 0) {
         const float r = L > 0.f ? A / L : 0.f;
         const long long oi = ((long long)b * Hq + hq) * D + d;
         if (out_mode == 0) ((float *)out)[oi] = r;
@@ -457,8 +494,8 @@ kv_attn_combine_kernel(const float *__restrict__ part_acc, const float *__restri
 
 int pick_gt(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
 
-// Tokens per split: a multiple of the rows one workgroup iteration covers.
-int split_quantum(int D) { return kWaves * kTile * tiles_per_iter(D); }
+// Tokens per split are a multiple of this: half a round of the workgroup's wavefronts.
+int split_quantum(int D) { return kWaves / 2 * kTile * tiles_per_step(D); }
 
 // Most splits the automatic choice can make for sequences of up to max_len tokens (sizes the workspace).
 int max_auto_splits(const kv_plan *p, int max_len)
@@ -467,15 +504,30 @@ int max_auto_splits(const kv_plan *p, int max_len)
     return (int)std::min<long long>(kMaxSplits, std::max<long long>(1, ((long long)max_len + q - 1) / q));
 }
 
-// Split length from the total token count, so that about 512 workgroups (two per compute unit; the
-// measured best at the 4K, 8K and 32K shapes) have tokens to read even when the batch is ragged;
-// never shorter than one workgroup iteration.
+// Workgroups the automatic split choice aims at: one per compute unit (a workgroup is eight wavefronts; with
+// one per compute unit every one of them starts at once and none waits for a second round).
+int target_workgroups()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+// Uniform batch: split length from the total token count, so that about one workgroup per compute unit has
+// tokens to read; never shorter than the quantum.
 int choose_splits(const kv_plan *p, long long total_tokens, int max_len)
 {
     if (max_len <= 0) return 1;
     const int q = split_quantum(p->D);
     const long long groups_per_seq = p->Hq / pick_gt(p->Hq / p->H);
-    long long st = (total_tokens * groups_per_seq + 511) / 512;
+    const long long wgs = target_workgroups();
+    long long st = (total_tokens * groups_per_seq + wgs - 1) / wgs;
     st = std::max<long long>(q, (st + q - 1) / q * q);
     const long long ns = ((long long)max_len + st - 1) / st;
     return (int)std::min<long long>(std::max<long long>(1, ns), max_auto_splits(p, max_len));
@@ -489,24 +541,64 @@ int split_tokens_for(const kv_plan *p, int n_splits, int max_len)
     return (int)std::max<long long>(st, q);
 }
 
+// Ragged batch of up to kMaxTableSeqs sequences: every sequence with tokens gets one split; the remaining
+// workgroups of the budget (one per compute unit, shared by the query-head groups) go, one at a time, to the
+// sequence whose splits are longest; no sequence gets more than cap splits or splits shorter than the quantum.
+// Returns the largest split count.
+int apportion_splits(const kv_plan *p, const int32_t *lens, int cap, SplitTable *t)
+{
+    const int q = split_quantum(p->D);
+    const long long groups_per_seq = p->Hq / pick_gt(p->Hq / p->H);
+    int nb[kMaxTableSeqs];
+    long long used = 0;
+    for (int b = 0; b < p->B; ++b) { nb[b] = lens[b] > 0 ? 1 : 0; used += nb[b]; }
+    const long long budget = std::max<long long>(used, target_workgroups() / groups_per_seq);
+    while (used < budget) {
+        int best = -1;
+        double longest = 0.0;
+        for (int b = 0; b < p->B; ++b) {
+            if (nb[b] == 0 || nb[b] >= cap || (long long)(nb[b] + 1) * q > (long long)lens[b] + q - 1) continue;
+            const double cur = (double)lens[b] / nb[b];
+            if (cur > longest) { longest = cur; best = b; }
+        }
+        if (best < 0) break;
+        ++nb[best];
+        ++used;
+    }
+    int most = 1, first = 0;
+    for (int b = 0; b < p->B; ++b) {
+        t->first[b] = first;
+        int st = q;
+        if (nb[b] > 0) {
+            st = (int)((((long long)lens[b] + nb[b] - 1) / nb[b] + q - 1) / q * q);
+            nb[b] = (lens[b] + st - 1) / st;   // rounding the split length up may leave fewer splits
+        }
+        t->tokens[b] = st;
+        first += nb[b];
+        most = std::max(most, nb[b]);
+    }
+    for (int b = p->B; b <= kMaxTableSeqs; ++b) t->first[b] = first;
+    return most;
+}
+
 template <int D, int GT>
-void launch_partial(bool bf16, bool paged, dim3 grid, hipStream_t st, const AttnParams &a)
+void launch_partial(bool bf16, bool paged, dim3 grid, hipStream_t st, const AttnParams &a, const SplitTable &t)
 {
     if (bf16) {
-        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, true, true>), grid, dim3(kThreads), 0, st, a);
-        else hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, true, false>), grid, dim3(kThreads), 0, st, a);
+        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, true, true>), grid, dim3(kThreads), 0, st, a, t);
+        else hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, true, false>), grid, dim3(kThreads), 0, st, a, t);
     } else {
-        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, false, true>), grid, dim3(kThreads), 0, st, a);
-        else hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, false, false>), grid, dim3(kThreads), 0, st, a);
+        if (paged) hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, false, true>), grid, dim3(kThreads), 0, st, a, t);
+        else hipLaunchKernelGGL((kv_attn_partial_kernel<D, GT, false, false>), grid, dim3(kThreads), 0, st, a, t);
     }
 }
 
 template <int D>
-void launch_partial_gt(int gt, bool bf16, bool paged, dim3 grid, hipStream_t st, const AttnParams &a)
+void launch_partial_gt(int gt, bool bf16, bool paged, dim3 grid, hipStream_t st, const AttnParams &a, const SplitTable &t)
 {
-    if (gt == 4) launch_partial<D, 4>(bf16, paged, grid, st, a);
-    else if (gt == 2) launch_partial<D, 2>(bf16, paged, grid, st, a);
-    else launch_partial<D, 1>(bf16, paged, grid, st, a);
+    if (gt == 4) launch_partial<D, 4>(bf16, paged, grid, st, a, t);
+    else if (gt == 2) launch_partial<D, 2>(bf16, paged, grid, st, a, t);
+    else launch_partial<D, 1>(bf16, paged, grid, st, a, t);
 }
 
 }  // namespace
@@ -519,6 +611,37 @@ extern "C" size_t kv_decode_attn_workspace(const kv_plan_t *p, int n_splits, int
 }
 
 namespace {
+
+// Split choice for the given lengths: fills the table (ragged batches of up to kMaxTableSeqs sequences) or the
+// common split length; returns the split count the partials are laid out for.
+int plan_splits(const kv_plan *p, const int32_t *lens, int n_splits, bool *use_table, SplitTable *tab, int *split_tokens)
+{
+    int max_len = 0;
+    long long total_len = 0;
+    bool uniform = true;
+    for (int b = 0; b < p->B; ++b) {
+        max_len = std::max(max_len, lens[b]);
+        total_len += lens[b];
+        if (lens[b] != lens[0]) uniform = false;
+    }
+    *use_table = !uniform && p->B <= kMaxTableSeqs;
+    if (*use_table && n_splits == 0) {
+        *split_tokens = split_quantum(p->D);  // not used by the kernels in table mode
+        return apportion_splits(p, lens, max_auto_splits(p, max_len), tab);
+    }
+    const int ns = n_splits > 0 ? n_splits : choose_splits(p, total_len, max_len);
+    *split_tokens = split_tokens_for(p, ns, max_len);
+    if (*use_table) {
+        int first = 0;
+        for (int b = 0; b < p->B; ++b) {
+            tab->first[b] = first;
+            tab->tokens[b] = *split_tokens;
+            first += (lens[b] + *split_tokens - 1) / *split_tokens;
+        }
+        for (int b = p->B; b <= kMaxTableSeqs; ++b) tab->first[b] = first;
+    }
+    return ns;
+}
 
 // Checks, split choice and the two launches; shared by both entry points.  Allocates nothing.
 int decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *q, void *out, int out_dtype,
@@ -536,12 +659,10 @@ int decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *
     if (p->B > 65535 || p->Hq > 65535) return KV_EINVAL;
 
     int max_len = 0;
-    long long total_len = 0;
     for (int b = 0; b < p->B; ++b) {
         const int len = kv->seq_lens_host[b];
         if (len < 0) return KV_EINVAL;
         max_len = std::max(max_len, len);
-        total_len += len;
     }
     AttnParams a{};
     const bool paged = kv->layout == KV_LAYOUT_PAGED;
@@ -575,45 +696,54 @@ int decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *
         return KV_EINVAL;
     }
 
-    const int ns = n_splits > 0 ? n_splits : choose_splits(p, total_len, max_len);
+    a.len_uniform = max_len;
+    for (int b = 0; b < p->B; ++b)
+        if (kv->seq_lens_host[b] != max_len) a.len_uniform = -1;
+
+    // Splits.  A uniform batch (or a split count given by the caller) takes one split length for all sequences
+    // and the grid (split, query-head group, sequence).  A ragged batch of up to 64 sequences launches
+    // workgroups only for splits that hold tokens: the x dimension of its grid walks a table of per-sequence
+    // split counts, and with the automatic choice each sequence's split length is sized so that every
+    // workgroup reads about the same number of tokens.
+    SplitTable tab{};
+    bool use_table = false;
+    const int ns = plan_splits(p, kv->seq_lens_host, n_splits, &use_table, &tab, &a.split_tokens);
+    a.use_table = use_table;
     const size_t need = (size_t)p->B * p->Hq * ns * (p->D + 2) * sizeof(float);
     if (ws_bytes < need) return KV_ENOSPC;
 
     const int G = p->Hq / p->H, gt = pick_gt(G);
     a.K = (const u32x4 *)K; a.V = (const u32x4 *)V; a.q = (const u32x4 *)q;
     a.seq_lens = kv->seq_lens_dev;
-    a.len_uniform = max_len;
-    for (int b = 0; b < p->B; ++b)
-        if (kv->seq_lens_host[b] != max_len) a.len_uniform = -1;
     a.part_acc = (float *)workspace;
     a.part_ml = a.part_acc + (size_t)p->B * p->Hq * ns * p->D;
     a.H = p->H; a.Hq = p->Hq; a.G = G; a.B = p->B;
     a.n_splits = ns;
     a.max_len = max_len;
-    a.split_tokens = split_tokens_for(p, ns, max_len);
     a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)p->D));
 
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf16 = p->dtype == KV_BF16;
-    // A ragged batch of up to 64 sequences launches workgroups only for the splits that hold tokens (placed
-    // over the compute units evenly); otherwise the grid is (split, query-head group, sequence).
-    long long n_items = 0;
-    for (int b = 0; b < p->B; ++b) n_items += (std::min(kv->seq_lens_host[b], max_len) + a.split_tokens - 1) / a.split_tokens;
-    a.compact = a.len_uniform < 0 && p->B <= 64;
+    const long long n_items = a.use_table ? tab.first[p->B] : (max_len > 0 ? (long long)ns * p->B : 0);
     dim3 grid((unsigned)ns, (unsigned)(p->Hq / gt), (unsigned)p->B);
-    if (a.compact) grid = dim3((unsigned)n_items, (unsigned)(p->Hq / gt), 1u);
+    if (a.use_table) grid = dim3((unsigned)n_items, (unsigned)(p->Hq / gt), 1u);
     if (n_items > 0) {
-        if (p->D == 64) launch_partial_gt<64>(gt, bf16, paged, grid, st, a);
-        else if (p->D == 128) launch_partial_gt<128>(gt, bf16, paged, grid, st, a);
-        else launch_partial_gt<256>(gt, bf16, paged, grid, st, a);
+        if (p->D == 64) launch_partial_gt<64>(gt, bf16, paged, grid, st, a, tab);
+        else if (p->D == 128) launch_partial_gt<128>(gt, bf16, paged, grid, st, a, tab);
+        else launch_partial_gt<256>(gt, bf16, paged, grid, st, a, tab);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
     }
 
     const int out_mode = out_dtype == KV_OUT_F32 ? 0 : (bf16 ? 2 : 1);
-    hipLaunchKernelGGL(kv_attn_combine_kernel, dim3((unsigned)p->Hq, (unsigned)p->B, (unsigned)(p->D / kCombineCols)), dim3(kCombineThreads), 0,
-                       st, a.part_acc, a.part_ml, out, p->Hq, p->D, ns, out_mode, a.seq_lens, a.len_uniform, max_len,
-                       a.split_tokens);
+    const dim3 cgrid((unsigned)p->Hq, (unsigned)p->B, 1u);
+#define KV_COMBINE(DD)                                                                                                   \
+    hipLaunchKernelGGL((kv_attn_combine_kernel<DD>), cgrid, dim3(kCombineThreads), 0, st, a.part_acc, a.part_ml, out,   \
+                       p->Hq, ns, out_mode, a.seq_lens, a.len_uniform, max_len, a.split_tokens, a.use_table, tab)
+    if (p->D == 64) KV_COMBINE(64);
+    else if (p->D == 128) KV_COMBINE(128);
+    else KV_COMBINE(256);
+#undef KV_COMBINE
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
     return KV_OK;
@@ -628,6 +758,28 @@ void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, r
 // Split partials of kv_decode_attn_static: every GPU the library runs on holds its own copy of this array
 // until the process ends.  In host code the name is only a handle for hipGetSymbolAddress.
 static __device__ __align__(256) unsigned char scratch[KV_ATTN_SCRATCH_BYTES];
+
+extern "C" int kv_decode_attn_splits(const kv_plan_t *p, const int32_t *seq_lens_host, int n_splits, int *n_splits_out,
+                                     int *first, int *tokens)
+{
+    if (!p || !seq_lens_host || !n_splits_out) return KV_EINVAL;
+    if (n_splits < 0 || n_splits > kMaxSplits) return KV_EINVAL;
+    if (p->D != 64 && p->D != 128 && p->D != 256) return KV_EINVAL;
+    for (int b = 0; b < p->B; ++b)
+        if (seq_lens_host[b] < 0) return KV_EINVAL;
+    SplitTable tab{};
+    bool use_table = false;
+    int st = 0;
+    *n_splits_out = plan_splits(p, seq_lens_host, n_splits, &use_table, &tab, &st);
+    int acc = 0;
+    for (int b = 0; b < p->B; ++b) {
+        if (first) first[b] = acc;
+        if (tokens) tokens[b] = use_table ? tab.tokens[b] : st;
+        acc += use_table ? tab.first[b + 1] - tab.first[b] : std::min(*n_splits_out, (seq_lens_host[b] + st - 1) / st);
+    }
+    if (first) first[p->B] = acc;
+    return KV_OK;
+}
 
 extern "C" int kv_decode_attn(const kv_plan_t *p, const kv_view_t *kv, int layer, const void *q, void *out,
                               int out_dtype, int n_splits, void *workspace, size_t ws_bytes, void *hip_stream)

@@ -352,6 +352,27 @@ def test_decode_attention_many_ragged_sequences(B, n_splits):
 
 # ------------------------------------------------------------------------------------------ pipeline
 # (span_chunks, depth, copy_streams, d2h_mode, h2d_mode)
+@pytest.mark.parametrize("D,G", [(64, 1), (64, 4), (128, 2), (128, 8), (256, 1), (256, 4)])
+@pytest.mark.parametrize("paged", [False, True], ids=["bhsd", "paged"])
+def test_decode_attention_long_splits_every_head_shape(D, G, paged):
+    """Splits long enough that the wavefronts of a workgroup claim steps on demand (more than two rounds of eight),
+    for every head width and query-group size the kernel is instantiated for, ragged (per-sequence split table)
+    and uniform, automatic and given split counts."""
+    H = 2
+    for i, lens in enumerate(([5000, 37, 1201], [2100], [777, 777])):
+        cfg = W.KVConfig(f"attn_D{D}_G{G}", 900 + 7 * i + D + G, 1, H, H * G, D, len(lens), W.BF16 if (D + G + i) % 2 else W.F16,
+                         512, 8, 2, W.PER_SEQ, W.PAGED if paged else W.BHSD, 0, len_range=(1, 2))
+        case = Case(cfg, "cuda", lens=list(lens))
+        q = W.query(cfg, 0, "cpu")
+        want = case.expected_attention(0, q)
+        for n_splits in (0, 2):
+            out = torch.full((len(lens), H * G, D), float("nan"), dtype=torch.float32, device="cuda")
+            ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, n_splits, max(lens)), dtype=torch.uint8, device="cuda")
+            kv.kv_decode_attn(case.plan, case.view, 0, q.cuda(), out, kv.KV_OUT_F32, n_splits, ws)
+            torch.cuda.synchronize()
+            _attn_check(out, want)
+
+
 PIPE_VARIANTS = [(0, 3, 0, kv.KV_COPY_AUTO, kv.KV_COPY_AUTO),
                  (1, 2, 1, kv.KV_COPY_MEMCPY, kv.KV_COPY_MEMCPY),
                  (2, 4, 3, kv.KV_COPY_KERNEL, kv.KV_COPY_KERNEL),

@@ -363,3 +363,45 @@ def test_budget_sample_system_and_cgroup_limits(tmp_path):
     # the real host: plausible figures
     a, m, s_ = kv.kv_budget_sample()
     assert 0 < a <= m * 2 and m > 0 and s_ >= 0
+
+
+def test_decode_attention_split_planning():
+    """Host arithmetic of the split choice (no GPU): the splits of every sequence tile its tokens exactly, split
+    lengths are multiples of the kernel's quantum, a ragged batch is cut so that the longest split is close to the
+    mean load of the workgroup budget, and a given split count is honoured."""
+    import random
+    rnd = random.Random(7)
+    for D, q in ((64, 128), (128, 64), (256, 64)):
+        for trial in range(40):
+            B = rnd.choice([1, 2, 3, 8, 17, 64, 70])
+            H = rnd.choice([1, 2, 8])
+            G = rnd.choice([1, 2, 4, 8])
+            uniform = rnd.random() < 0.3
+            n0 = rnd.randint(0, 9000)
+            lens = [n0] * B if uniform else [rnd.choice([0, 1, rnd.randint(1, 9000)]) for _ in range(B)]
+            plan = kv.kv_layout_plan(1, H, H * G, D, [max(max(lens), 1)] * B, kv.KV_F16, 512, 8)
+            for n_splits in (0, 1, 5):
+                ns, first, tokens = kv.kv_decode_attn_splits(plan, lens, n_splits)
+                assert 1 <= ns <= 1024 and first[0] == 0
+                if n_splits:
+                    assert ns == n_splits
+                for b, n in enumerate(lens):
+                    nb, st = first[b + 1] - first[b], tokens[b]
+                    assert st % q == 0 and st >= q
+                    assert nb <= ns and nb == -(-n // st)              # exactly the splits that hold tokens
+                    assert nb * st >= n and (nb == 0 or (nb - 1) * st < n)
+                ragged = len(set(lens)) > 1
+                if n_splits == 0 and ragged and B <= 64 and sum(lens) > 0:
+                    groups = (H * G) // (4 if G % 4 == 0 else 2 if G % 2 == 0 else 1)
+                    budget = max(sum(1 for n in lens if n > 0), 256 // groups)   # 256 workgroups when no GPU is present
+                    assert first[B] <= budget
+                    nbs = [first[b + 1] - first[b] for b in range(B)]
+                    longest = max(min(tokens[b], lens[b]) for b in range(B))
+                    assert longest >= sum(lens) / budget - q               # cannot beat the mean load
+                    # minimax: taking a split away from any sequence would make that sequence's splits at least as
+                    # long as the longest split now (up to the rounding of split lengths to the quantum)
+                    for b in range(B):
+                        if nbs[b] >= 2:
+                            assert longest <= lens[b] / (nbs[b] - 1) + q
+    with pytest.raises(kv.KVError):
+        kv.kv_decode_attn_splits(plan, [-1] * len(lens), 0)
