@@ -21,13 +21,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --leg kernels` on the
-# llama8b_32k workload (profiles/pmc_traffic_llama8b_32k.md), each counter scaled by what it reads for a
-# plain 128 MiB device-to-device copy in the same run.  Valid only for the kernel sources they were taken
-# with: the hash below covers the two kernel files, and a mismatch reports traffic as null.
-PMC_TRAFFIC = {"sha": "540b7d6a921b615a", "workload": "llama8b_32k",
-               "kv_layout_kernel<pack>": 268486797, "kv_layout_kernel<unpack>": 268468985,
-               "kv_attn_partial_kernel+kv_attn_combine_kernel": 135508062 + 1147700}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --leg kernels` on each
+# workload (profiles/pmc_traffic_<workload>.md), each counter scaled by what it reads for a plain device-to-device
+# copy of known size in the same run.  Valid only for the kernel sources they were taken with: the hash below
+# covers the two kernel files, and a mismatch reports traffic as null.
+PMC_TRAFFIC = {"sha": "2bd7b292b4d5d133",
+               "llama8b_32k": {"kv_layout_kernel<pack>": 268504345, "kv_layout_kernel<unpack>": 268453928, "kv_attn_partial_kernel+kv_attn_combine_kernel": 135566078},
+               "llama8b_4k": {"kv_layout_kernel<pack>": 268551020, "kv_layout_kernel<unpack>": 268453465, "kv_attn_partial_kernel+kv_attn_combine_kernel": 18142084},
+               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282194183, "kv_layout_kernel<unpack>": 282059531, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142742520},
+               "gemma7b_mha_8k": {"kv_layout_kernel<pack>": 536933694, "kv_layout_kernel<unpack>": 536903903, "kv_attn_partial_kernel+kv_attn_combine_kernel": 538923801}}
 
 
 def kernel_sources_hash() -> str:
@@ -53,11 +55,14 @@ def measure_link(torch, total_bytes: int, piece: int = 64 << 20):
     for name, (dst, src) in {"h2d": (dev, host), "d2h": (host, dev)}.items():
         dst.copy_(src, non_blocking=True)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n):
-            dst.copy_(src, non_blocking=True)
-        torch.cuda.synchronize()
-        out[name] = n * piece / (time.perf_counter() - t0) / 1e9
+        best = 0.0
+        for _ in range(3):   # the ceiling is the best of three passes (a pass now and then runs 10 % low)
+            t0 = time.perf_counter()
+            for _ in range(n):
+                dst.copy_(src, non_blocking=True)
+            torch.cuda.synchronize()
+            best = max(best, n * piece / (time.perf_counter() - t0) / 1e9)
+        out[name] = best
     return out
 
 
@@ -375,7 +380,7 @@ def main():
         res["host_link"] = {"h2d_GBps": round(link["h2d"], 2), "d2h_GBps": round(link["d2h"], 2),
                             "offload_frac": round(off_gbps / link["d2h"], 3),
                             "reload_frac": round(rel_gbps / link["h2d"], 3),
-                            "how": "back-to-back pinned 64 MiB copies, no kernels, same run"}
+                            "how": "back-to-back pinned 64 MiB copies, no kernels, same run, best of three passes"}
 
         # per-path throughput (outside the timed region): page-cache-path layers and direct-path layers alone
         per_path = {}
@@ -457,9 +462,9 @@ def main():
         rl = [roof("kv_layout_kernel<pack>", kl["pack_us"], tpl * (tensor_payload + tensor_image), where),
               roof("kv_layout_kernel<unpack>", kl["unpack_us"], tpl * 2 * tensor_payload, where),
               roof("kv_attn_partial_kernel+kv_attn_combine_kernel", kl["attn_us"], 2 * tensor_payload, where)]
-        if cfg.name == PMC_TRAFFIC["workload"] and kernel_sources_hash() == PMC_TRAFFIC["sha"]:
+        if cfg.name in PMC_TRAFFIC and kernel_sources_hash() == PMC_TRAFFIC["sha"]:
             for r in rl:
-                r["traffic"] = PMC_TRAFFIC.get(r["kernel"])
+                r["traffic"] = PMC_TRAFFIC[cfg.name].get(r["kernel"])
         res["rooflines"] = rl
         res["decode_attn_us_per_layer"] = round(kl["attn_us"], 2)
         # the dominant kernel of a step: the one with the most GPU time over its launches
