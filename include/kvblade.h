@@ -205,6 +205,9 @@ typedef struct kv_pipe_stats {
                                  previous one ended (Sec. IV-B "Sequential-LBA Placement": 0 for KV_ORDER_CROSS,
                                  the bind recurrence makes the whole stream one ascending run) */
     uint32_t reserved;
+    double host_copy_wait_s;  /* time the issuing thread waited for the page-cache path's memcpy hop (a bounce slot
+                                 still being copied out of, or not yet filled): 0 when that hop keeps ahead of the link */
+    double harvest_wait_s;    /* time the issuing thread waited for the oldest command's completion */
 } kv_pipe_stats_t;
 
 /* ------------------------------------------------------------------------------------------ */

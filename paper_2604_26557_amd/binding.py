@@ -99,7 +99,8 @@ class kv_pipe_stats_t(C.Structure):
                 ("n_chunks", C.c_uint32), ("n_spans", C.c_uint32), ("max_in_flight", C.c_uint32),
                 ("group_seconds", C.c_double * 2),
                 ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4),
-                ("lba_seq_breaks", C.c_uint32), ("reserved", C.c_uint32)]
+                ("lba_seq_breaks", C.c_uint32), ("reserved", C.c_uint32),
+                ("host_copy_wait_s", C.c_double), ("harvest_wait_s", C.c_double)]
 
 
 class kv_adapt_t(C.Structure):

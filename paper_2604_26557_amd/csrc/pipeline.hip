@@ -90,19 +90,18 @@ struct CopyTask {
     void *dst;
     const void *src;
     size_t bytes;
-    hipEvent_t wait_ev;  // DMA that must land first (offload), or nullptr
     std::atomic<int> *pending;
 };
 
 // Host threads of the page-cache path's memcpy hop.
 class Workers {
 public:
-    void start(int n, int device)
+    void start(int n)
     {
         if ((int)threads_.size() == n) return;
         stop();
         quit_ = false;
-        for (int i = 0; i < n; ++i) threads_.emplace_back([this, device] { loop(device); });
+        for (int i = 0; i < n; ++i) threads_.emplace_back([this] { loop(); });
     }
     void stop()
     {
@@ -114,31 +113,46 @@ public:
         for (auto &t : threads_) t.join();
         threads_.clear();
     }
-    void push(const CopyTask &t)
+    // All pieces of one command under one lock; sleeping threads are woken only if there are any, and no
+    // more of them than there are pieces (the issuing thread pays for every wake-up call).
+    void push(const CopyTask *t, int n)
     {
+        int wake = 0;
         {
             std::lock_guard<std::mutex> g(mu_);
-            q_.push_back(t);
+            for (int i = 0; i < n; ++i) q_.push_back(t[i]);
+            queued_.store((int)q_.size(), std::memory_order_release);
+            wake = std::min(n, sleeping_);
         }
-        cv_.notify_one();
+        if (wake >= (int)threads_.size()) cv_.notify_all();
+        else for (int i = 0; i < wake; ++i) cv_.notify_one();
     }
     int size() const { return (int)threads_.size(); }
     ~Workers() { stop(); }
 
 private:
-    void loop(int device)
+    void loop()
     {
-        (void)hipSetDevice(device);
         for (;;) {
             CopyTask t;
+            // pieces arrive every few tens of microseconds while a call runs, and a sleeping thread takes about
+            // that long to wake: poll the queue length for a short while before going to sleep
+            for (int spin = 0; spin < kSpinsBeforeSleep && queued_.load(std::memory_order_acquire) == 0; ++spin) __builtin_ia32_pause();
             {
                 std::unique_lock<std::mutex> g(mu_);
-                cv_.wait(g, [this] { return quit_ || !q_.empty(); });
-                if (q_.empty()) return;
+                if (q_.empty() && !quit_) {
+                    ++sleeping_;
+                    cv_.wait(g, [this] { return quit_ || !q_.empty(); });
+                    --sleeping_;
+                }
+                if (q_.empty()) {
+                    if (quit_) return;
+                    continue;
+                }
                 t = q_.front();
                 q_.pop_front();
+                queued_.store((int)q_.size(), std::memory_order_release);
             }
-            if (t.wait_ev) (void)hipEventSynchronize(t.wait_ev);
             std::memcpy(t.dst, t.src, t.bytes);
             t.pending->fetch_sub(1, std::memory_order_release);
         }
@@ -148,6 +162,9 @@ private:
     std::mutex mu_;
     std::condition_variable cv_;
     bool quit_ = false;
+    int sleeping_ = 0;  // threads inside cv_.wait (under mu_)
+    std::atomic<int> queued_{0};  // queue length, readable without the lock
+    static constexpr int kSpinsBeforeSleep = 4000;  // roughly 50-100 us
 };
 
 struct Chunk {
@@ -284,7 +301,7 @@ int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, si
         if (!e.ev) KV_HIP(hipEventCreateWithFlags(&e.ev, hipEventDisableTiming));
     rc = ensure_events(q->timing, n_timing, hipEventDefault);
     if (rc) return rc;
-    if (need_bounce) q->workers.start(n_workers, q->device);
+    if (need_bounce) q->workers.start(n_workers);
     return KV_OK;
 }
 
@@ -437,12 +454,16 @@ int order_after_caller(kv_pipeline *q, void *caller_stream)
     return KV_OK;
 }
 
-inline void spin_until_zero(std::atomic<int> &a)
+// Returns the seconds spent waiting (0 when the counter was already zero).
+inline double spin_until_zero(std::atomic<int> &a)
 {
+    if (a.load(std::memory_order_acquire) == 0) return 0.0;
+    const auto t0 = std::chrono::steady_clock::now();
     int spins = 0;
     while (a.load(std::memory_order_acquire) != 0) {
         if (++spins > 2000) std::this_thread::yield();
     }
+    return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
 }
 
 }  // namespace
@@ -598,6 +619,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const size_t N = chunks.size();
     std::vector<unsigned> slot_used(n_slots, 0u);  // copy streams that carried the slot's last span
     size_t n_waited = 0;  // chunks [0, n_waited) are known complete
+    size_t n_issued = 0;  // offload: chunks [0, n_issued) have been issued
     uint32_t max_in_flight = 0;
     int err = KV_OK;
 
@@ -608,10 +630,40 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         const int g = spans[chunks[c].span].path == KV_PATH_PAGECACHE ? 0 : 1;
         if (group_t0[g] < 0) group_t0[g] = now_s();
     };
+    auto host_ptr = [&](const Chunk &ch) -> char * {
+        return (spans[ch.span].path == KV_PATH_DIRECT ? (char *)lba_region : (char *)pageable) + ch.host_off;
+    };
+    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % NB) * bounce_slot; };
+    // The memcpy hop of chunk c, cut into pieces for the worker threads; ring entry c counts the pieces down.
+    auto fan_out = [&](size_t c, void *dst, const void *src, size_t bytes) {
+        Entry &e = q->ring[c % NB];
+        int pieces = (int)std::min<size_t>((size_t)pieces_max, std::max<size_t>(1, bytes / (256 * 1024)));
+        e.pending.store(pieces, std::memory_order_release);
+        const size_t step = kvb::round_up(kvb::ceil_div(bytes, (uint64_t)pieces), 4096);
+        CopyTask tasks[64];
+        size_t off = 0;
+        int n_tasks = 0;
+        for (int i = 0; i < pieces; ++i) {
+            const size_t n = off < bytes ? std::min(step, bytes - off) : 0;
+            if (n == 0) { e.pending.fetch_sub(1, std::memory_order_release); continue; }
+            tasks[n_tasks++] = CopyTask{(char *)dst + off, (const char *)src + off, n, &e.pending};
+            off += n;
+        }
+        q->workers.push(tasks, n_tasks);
+    };
+
     // Chunk c owns ring entry c % NB.  Transfers are harvested in issue order; n_waited counts them.
+    double host_wait_s = 0.0, harvest_wait_s = 0.0;
     auto harvest_until = [&](size_t upto) -> int {  // transfers of chunks [0, upto) are complete
         while (n_waited < upto) {
-            KV_HIP(hipEventSynchronize(q->ring[n_waited % NB].ev));
+            if (hipEventQuery(q->ring[n_waited % NB].ev) != hipSuccess) {
+                const double t0 = now_s();
+                KV_HIP(hipEventSynchronize(q->ring[n_waited % NB].ev));
+                harvest_wait_s += now_s() - t0;
+            }
+            // offload, page-cache path: the chunk's bytes are in its bounce slot now; start the memcpy hop
+            if (offload_dir && spans[chunks[n_waited].span].path == KV_PATH_PAGECACHE)
+                fan_out(n_waited, host_ptr(chunks[n_waited]), bounce_ptr(n_waited), chunks[n_waited].bytes);
             for (int g = 0; g < 2; ++g)
                 if ((long long)n_waited == group_last[g]) group_t1[g] = now_s();
             ++n_waited;
@@ -625,30 +677,9 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (c < NB) return KV_OK;
         int r = harvest_until(c - NB + 1);
         if (r != KV_OK) return r;
-        spin_until_zero(q->ring[c % NB].pending);
+        host_wait_s += spin_until_zero(q->ring[c % NB].pending);
         return KV_OK;
     };
-    auto host_ptr = [&](const Chunk &ch) -> char * {
-        return (spans[ch.span].path == KV_PATH_DIRECT ? (char *)lba_region : (char *)pageable) + ch.host_off;
-    };
-    auto bounce_ptr = [&](size_t c) -> char * { return (char *)q->bounce + (c % NB) * bounce_slot; };
-    auto fan_out = [&](size_t c, void *dst, const void *src, size_t bytes, hipEvent_t ev) {
-        Entry &e = q->ring[c % NB];
-        int pieces = (int)std::min<size_t>((size_t)pieces_max, std::max<size_t>(1, bytes / (256 * 1024)));
-        e.pending.store(pieces, std::memory_order_release);
-        const size_t step = kvb::round_up(kvb::ceil_div(bytes, (uint64_t)pieces), 4096);
-        size_t off = 0;
-        int pushed = 0;
-        for (int i = 0; i < pieces; ++i) {
-            const size_t n = off < bytes ? std::min(step, bytes - off) : 0;
-            if (n == 0) { e.pending.fetch_sub(1, std::memory_order_release); continue; }
-            q->workers.push(CopyTask{(char *)dst + off, (const char *)src + off, n, ev, &e.pending});
-            off += n;
-            ++pushed;
-        }
-        (void)pushed;
-    };
-
     // Transfer of one chunk command on copy stream `st`; `ev` is its completion entry.  The copy kernel carries
     // the event on its own dispatch (no separate record packet: measured +5-14 % on commands of 1 MiB and less).
     auto issue_copy = [&](void *dst, const void *src, size_t bytes, bool to_host, hipStream_t st, hipEvent_t ev) -> hipError_t {
@@ -717,13 +748,16 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             if (sp.path == KV_PATH_DIRECT) {
                 KV_HIP_BRK(issue_copy(host_ptr(ch), img + ch.stage_off, ch.bytes, true, st, e.ev));
             } else {
+                // the memcpy hop starts when this transfer is harvested (its bytes are in the bounce slot then);
+                // until then the entry counts one outstanding host copy
                 KV_HIP_BRK(issue_copy(bounce_ptr(c), img + ch.stage_off, ch.bytes, true, st, e.ev));
-                fan_out(c, host_ptr(ch), bounce_ptr(c), ch.bytes, e.ev);
+                e.pending.store(1, std::memory_order_release);
             }
+            n_issued = c + 1;
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(c + 1 - n_waited));
             if (serialize) {  // every stage to completion before the next starts
                 if ((err = harvest_until(c + 1)) != KV_OK) break;
-                spin_until_zero(e.pending);
+                host_wait_s += spin_until_zero(e.pending);
             }
             if (ch.last) {
                 for (int k = 0; k < ns && err == KV_OK; ++k)
@@ -747,7 +781,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 if ((err = entry_free(cs)) != KV_OK) break;
                 note_issue(cs);
                 Entry &e = q->ring[cs % NB];
-                if (pc) fan_out(cs, bounce_ptr(cs), host_ptr(chunks[cs]), chunks[cs].bytes, nullptr);
+                if (pc) fan_out(cs, bounce_ptr(cs), host_ptr(chunks[cs]), chunks[cs].bytes);
                 else e.pending.store(0, std::memory_order_release);
                 ++cs;
             }
@@ -768,7 +802,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
             if (sp.path == KV_PATH_DIRECT) {
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, host_ptr(ch), ch.bytes, false, st, e.ev));
             } else {
-                spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
+                host_wait_s += spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st, e.ev));
             }
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(ci + 1 - n_waited));
@@ -855,6 +889,15 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (ek != hipSuccess) e1 = ek;
     }
     hipError_t e2 = hipStreamSynchronize(q->s_compute);
+    if (offload_dir) {
+        // every issued transfer has landed: harvest the rest, which starts their memcpy hops (after an error the
+        // events may not all be usable: the hops of what was issued are started directly)
+        if (err != KV_OK || harvest_until(n_issued) != KV_OK) {
+            for (; n_waited < n_issued; ++n_waited)
+                if (spans[chunks[n_waited].span].path == KV_PATH_PAGECACHE)
+                    fan_out(n_waited, host_ptr(chunks[n_waited]), bounce_ptr(n_waited), chunks[n_waited].bytes);
+        }
+    }
     for (auto &e : q->ring) spin_until_zero(e.pending);
     if (err == KV_OK && (e1 != hipSuccess || e2 != hipSuccess)) {
         kvb::set_hip_error((int)(e1 != hipSuccess ? e1 : e2));
@@ -867,6 +910,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         stats->group_seconds[1] = group_t0[1] >= 0 ? group_t1[1] - group_t0[1] : 0.0;
         stats->max_in_flight = max_in_flight;
         stats->lba_seq_breaks = sched.lba_seq_breaks;
+        stats->host_copy_wait_s = host_wait_s;
+        stats->harvest_wait_s = harvest_wait_s;
         if (time_kernels && err == KV_OK) {
             for (size_t i = 0; i < timing_kind.size(); ++i) {
                 float ms = 0.f;
