@@ -333,8 +333,8 @@ size_t kv_decode_attn_workspace(const kv_plan_t *plan, int n_splits, int max_len
  * sequence's first split among the splits that hold tokens, first[B] = their number (workgroups launched per
  * query-head group); tokens (host [B], nullable) = token rows per split of each sequence.  Host arithmetic only.
  * A uniform batch, or a given n_splits, takes one split length for all sequences; a ragged batch of up to 64
- * sequences with n_splits = 0 gets per-sequence split lengths such that every workgroup reads about the same
- * number of tokens (about one workgroup per compute unit in all).
+ * sequences with n_splits = 0 gets per-sequence split lengths (whole 16-token tiles, 32 tokens for head_dim 64) such
+ * that every workgroup reads about the same number of tokens (about one workgroup per compute unit in all).
  */
 int kv_decode_attn_splits(const kv_plan_t *plan, const int32_t *seq_lens_host, int n_splits, int *n_splits_out,
                           int *first, int *tokens);

@@ -6,17 +6,18 @@
 //  * DMA runs per chunk command; at most `depth` commands are outstanding (the queue-depth rule:
 //    when `depth` are in flight the oldest is harvested before the next is issued; a final drain
 //    collects the rest).  hipEvents play the role of completion-queue entries.
-//  * Kernels run per span = a whole tensor, or K and V of a layer together while the pair is at most
-//    256 MiB, by default (HBM is large, so staging whole extents costs nothing and the pack / unpack
-//    launches are big enough to run at HBM speed), or every `span_chunks` chunks of one tensor on request.
+//  * Kernels run per span = a whole tensor, K and V of a layer together while the pair is at most
+//    256 MiB, or several small layers of one path together, by default (HBM is large, so staging whole
+//    extents costs nothing and the pack / unpack launches are big enough to run at HBM speed), or every
+//    `span_chunks` chunks of one tensor on request.
 // Streams: one for kernels and up to four for copies (chunk c goes to copy stream c mod n, so the
 // start-up and tail of one transfer hide behind the next); events order pack -> D2H and
 // H2D -> unpack -> attention and guard staging-slot reuse.  All streams keep the default priority.
-// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D is fastest as
-// hipMemcpyAsync over four streams; D2H of small commands is fastest as this file's own copy kernel
-// over three streams, its completion event attached to the dispatch (the runtime's per-command cost
-// dominates D2H copies of a few hundred KiB), D2H of large commands as hipMemcpyAsync over up to four
-// streams.  Both engines are options.
+// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): commands of up to 1 MiB move
+// fastest, in both directions, as this file's own copy kernel (three streams D2H, two H2D; its completion
+// event rides on the dispatch: the runtime's per-command cost dominates copies of a few hundred KiB);
+// larger ones as hipMemcpyAsync over up to four streams (D2H from 2 MiB at depth >= 4, else from 8 MiB).
+// Both engines are options.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
@@ -506,9 +507,10 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const int d2h_mode = opts ? opts->d2h_mode : KV_COPY_AUTO, h2d_mode = opts ? opts->h2d_mode : KV_COPY_AUTO;
     if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
         return KV_EINVAL;
-    // Engine defaults by measurement: H2D is fastest as hipMemcpyAsync over four streams at every chunk
-    // size; D2H is fastest as hipMemcpyAsync over up to four streams for commands of 8 MiB and more, and
-    // of 2 MiB and more when four may be in flight; as the copy kernel over three streams otherwise.
+    // Engine defaults by measurement: H2D as the copy kernel over two streams for commands of up to 1 MiB, as
+    // hipMemcpyAsync over four streams above; D2H as hipMemcpyAsync over up to four streams for commands of
+    // 8 MiB and more, and of 2 MiB and more when four may be in flight; as the copy kernel over three streams
+    // otherwise.
     uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
     uint64_t cmd_limit = UINT64_MAX;  // Eq. 7 on the caller's transfer-size limit
     if (opts && opts->max_cmd_bytes) {

@@ -367,11 +367,12 @@ def test_budget_sample_system_and_cgroup_limits(tmp_path):
 
 def test_decode_attention_split_planning():
     """Host arithmetic of the split choice (no GPU): the splits of every sequence tile its tokens exactly, split
-    lengths are multiples of the kernel's quantum, a ragged batch is cut so that the longest split is close to the
-    mean load of the workgroup budget, and a given split count is honoured."""
+    lengths are multiples of the kernel's quantum (of one step of the kernel, and at least the quantum, where a ragged
+    batch gets per-sequence lengths), a ragged batch is cut so that the longest split is close to the mean load of
+    the workgroup budget, and a given split count is honoured."""
     import random
     rnd = random.Random(7)
-    for D, q in ((64, 128), (128, 64), (256, 64)):
+    for D, q, step in ((64, 128, 32), (128, 64, 16), (256, 64, 16)):
         for trial in range(40):
             B = rnd.choice([1, 2, 3, 8, 17, 64, 70])
             H = rnd.choice([1, 2, 8])
@@ -385,9 +386,10 @@ def test_decode_attention_split_planning():
                 assert 1 <= ns <= 1024 and first[0] == 0
                 if n_splits:
                     assert ns == n_splits
+                per_seq = n_splits == 0 and len(set(lens)) > 1 and B <= 64
                 for b, n in enumerate(lens):
                     nb, st = first[b + 1] - first[b], tokens[b]
-                    assert st % q == 0 and st >= q
+                    assert st % (step if per_seq else q) == 0 and st >= q
                     assert nb <= ns and nb == -(-n // st)              # exactly the splits that hold tokens
                     assert nb * st >= n and (nb == 0 or (nb - 1) * st < n)
                 ragged = len(set(lens)) > 1
