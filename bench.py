@@ -25,11 +25,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # workload (profiles/pmc_traffic_<workload>.md), each counter scaled by what it reads for a plain device-to-device
 # copy of known size in the same run.  Valid only for the kernel sources they were taken with: the hash below
 # covers the two kernel files, and a mismatch reports traffic as null.
-PMC_TRAFFIC = {"sha": "2bd7b292b4d5d133",
-               "llama8b_32k": {"kv_layout_kernel<pack>": 268504345, "kv_layout_kernel<unpack>": 268453928, "kv_attn_partial_kernel+kv_attn_combine_kernel": 135566078},
-               "llama8b_4k": {"kv_layout_kernel<pack>": 268551020, "kv_layout_kernel<unpack>": 268453465, "kv_attn_partial_kernel+kv_attn_combine_kernel": 18142084},
-               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282194183, "kv_layout_kernel<unpack>": 282059531, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142742520},
-               "gemma7b_mha_8k": {"kv_layout_kernel<pack>": 536933694, "kv_layout_kernel<unpack>": 536903903, "kv_attn_partial_kernel+kv_attn_combine_kernel": 538923801}}
+PMC_TRAFFIC = {"sha": "f663734213d3c082",
+               "llama8b_32k": {"kv_layout_kernel<pack>": 268501489, "kv_layout_kernel<unpack>": 268458776, "kv_attn_partial_kernel+kv_attn_combine_kernel": 135566734},
+               "llama8b_4k": {"kv_layout_kernel<pack>": 268551112, "kv_layout_kernel<unpack>": 268454181, "kv_attn_partial_kernel+kv_attn_combine_kernel": 18132873},
+               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282195672, "kv_layout_kernel<unpack>": 282060312, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142719609},
+               "gemma7b_mha_8k": {"kv_layout_kernel<pack>": 536934390, "kv_layout_kernel<unpack>": 536903830, "kv_attn_partial_kernel+kv_attn_combine_kernel": 539587232}}
 
 
 def kernel_sources_hash() -> str:
