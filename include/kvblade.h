@@ -316,7 +316,8 @@ int kv_reload_unpack_layers(const kv_plan_t *plan, int layer_begin, int layer_en
  * V[b,h,j,:], j in [0, len_b), h = hq / (H_q/H); fp32 accumulation; split-K over tokens with a
  * combine pass.  len_b = kv->seq_lens_dev (device) with kv->seq_lens_host as its host mirror (both must
  * hold the same values: a batch whose sequences all have one length takes it from the host mirror at launch); a
- * sequence of length 0 yields zeros.
+ * sequence of length 0 yields zeros.  The wavefronts of a workgroup take their tiles on demand, so the order of the
+ * fp32 sums, and with it the last bits of the result, can differ between two runs on the same inputs.
  * q: device [B,H_q,D] 16-bit, 16-byte aligned; out: device [B,H_q,D] fp32 or 16-bit (out_dtype);
  * workspace: device, >= kv_decode_attn_workspace() bytes (else KV_ENOSPC); n_splits 0 = choose.
  */

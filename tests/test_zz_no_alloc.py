@@ -67,3 +67,42 @@ def test_static_scratch_entry_rejects_oversized_request():
     assert e.value.code == kv.KV_ENOSPC
     kv.kv_decode_attn_static(case.plan, case.view, 0, q, out, kv.KV_OUT_F32, too_many - 1)   # the largest that fits
     torch.cuda.synchronize()
+
+
+def test_static_scratch_entry_under_graph_capture():
+    """What the entry point is for: the attention launches of several layers recorded in one HIP graph.  The graph is
+    replayed several times, with eager launches and synchronisations of the same calls in between, and every replay
+    is checked against the eager result (the split partials of all layers pass through the one static array; results
+    may differ from run to run by rounding, since the wavefronts claim their steps on demand)."""
+    torch.cuda.set_device(0)
+    cfg = W.shrink(W.CONFIGS[3], n_layers=3, batch=3, len_range=(300, 1500))
+    print(f"graph-capture case {cfg.name} seed {cfg.seed}", flush=True)
+    case = Case(cfg, "cuda")
+    L = cfg.n_layers
+    q = [W.query(cfg, l, "cuda") for l in range(L)]
+    outs = [torch.zeros((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda") for _ in range(L)]
+
+    def run():
+        for l in range(L):
+            kv.kv_decode_attn_static(case.plan, case.view, l, q[l], outs[l], kv.KV_OUT_F32, 0)
+
+    run()                                   # eager: resolves the static array before anything is captured
+    torch.cuda.synchronize()
+    want = [o.double().cpu().numpy() for o in outs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l in range(L):
+            got = outs[l].double().cpu().numpy()
+            assert np.isfinite(got).all(), (replay, l)
+            err, scale = np.abs(got - want[l]).max(), np.abs(want[l]).max()
+            assert err <= 1e-5 * scale, (replay, l, err, scale)
+        run()                               # the program's own eager work between replays
+        torch.cuda.synchronize()
