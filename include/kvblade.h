@@ -169,6 +169,21 @@ typedef struct kv_attn_args {
 #define KV_ORDER_CROSS 0 /* per layer all of K's commands, then V's: V's storage-side hop overlaps K's transfers */
 #define KV_ORDER_INTRA 1 /* K's and V's commands alternate: both tensors' storage-side hops run side by side */
 
+/* One chunk command as the pipeline ran it (kv_pipe_opts_t.trace), in issue order.  Times are the issuing
+ * thread's clock in seconds since the call was entered: t_issue when the transfer was queued on its copy stream,
+ * t_done when its completion was harvested (completions are harvested in issue order, each when the depth rule
+ * or the final drain needs it, so t_done is an upper bound of the transfer's end). */
+typedef struct kv_chunk_trace {
+    uint64_t host_off;  /* byte offset in the LBA region (slba * sector) or in the arena */
+    uint64_t bytes;     /* (nlb + 1) * sector */
+    uint16_t layer;
+    uint8_t kind;       /* KV_K | KV_V */
+    uint8_t path;       /* KV_PATH_* */
+    uint32_t reserved;
+    double t_issue_s;
+    double t_done_s;
+} kv_chunk_trace_t;
+
 typedef struct kv_pipe_opts {
     int32_t span_chunks;  /* chunks of one tensor per kernel launch and staging slot; 0 = whole extents: K and V
                              of a layer in one launch, and consecutive layers of one path together while their
@@ -188,6 +203,11 @@ typedef struct kv_pipe_opts {
     void *caller_stream;     /* hipStream_t on which the caller produced (or still reads) the view's buffers, the
                                 queries and the block table; NULL = the default stream.  The library's own streams
                                 are ordered after everything queued on it when the call is entered */
+    kv_chunk_trace_t *trace; /* host, nullable: filled with the first trace_cap chunk commands of the call (the
+                                queue-depth rule of Sec. IV-B "Data Flow" can be read off it: command c is issued
+                                only after command c - depth was harvested); kv_pipe_stats_t.n_traced says how many */
+    uint32_t trace_cap;
+    uint32_t reserved;
 } kv_pipe_opts_t;
 
 typedef struct kv_pipe_stats {
@@ -204,7 +224,7 @@ typedef struct kv_pipe_stats {
     uint32_t lba_seq_breaks;  /* direct-path commands, in issue order, that do not start at the LBA where the
                                  previous one ended (Sec. IV-B "Sequential-LBA Placement": 0 for KV_ORDER_CROSS,
                                  the bind recurrence makes the whole stream one ascending run) */
-    uint32_t reserved;
+    uint32_t n_traced;        /* entries written to kv_pipe_opts_t.trace */
     double host_copy_wait_s;  /* time the issuing thread waited for the page-cache path's memcpy hop (a bounce slot
                                  still being copied out of, or not yet filled): 0 when that hop keeps ahead of the link */
     double harvest_wait_s;    /* time the issuing thread waited for the oldest command's completion */
@@ -464,7 +484,8 @@ const char *kv_strerror(int code); /* static string */
 int kv_abi_version(void);
 /* sizeof of the ABI struct number `which` as this library was compiled (0 kv_plan_desc_t, 1 kv_plan_info_t,
  * 2 kv_extent_t, 3 kv_cmd_t, 4 kv_view_t, 5 kv_attn_args_t, 6 kv_pipe_opts_t, 7 kv_pipe_stats_t,
- * 8 kv_append_stats_t, 9 kv_adapt_t; 0 for any other number): lets a binding verify its own layouts. */
+ * 8 kv_append_stats_t, 9 kv_adapt_t, 10 kv_chunk_trace_t; 0 for any other number): lets a binding verify its own
+ * layouts. */
 size_t kv_abi_sizeof(int which);
 
 #ifdef __cplusplus

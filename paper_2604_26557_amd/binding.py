@@ -87,11 +87,17 @@ class kv_attn_args_t(C.Structure):
                 ("out_dtype", C.c_int32), ("n_splits", C.c_int32)]
 
 
+class kv_chunk_trace_t(C.Structure):
+    _fields_ = [("host_off", C.c_uint64), ("bytes", C.c_uint64), ("layer", C.c_uint16), ("kind", C.c_uint8),
+                ("path", C.c_uint8), ("reserved", C.c_uint32), ("t_issue_s", C.c_double), ("t_done_s", C.c_double)]
+
+
 class kv_pipe_opts_t(C.Structure):
     _fields_ = [("span_chunks", C.c_int32), ("host_workers", C.c_int32), ("flags", C.c_uint32),
                 ("copy_streams", C.c_int32), ("d2h_mode", C.c_int32), ("h2d_mode", C.c_int32),
                 ("order_pagecache", C.c_int32), ("order_direct", C.c_int32), ("max_cmd_bytes", C.c_uint64),
-                ("caller_stream", C.c_void_p)]
+                ("caller_stream", C.c_void_p), ("trace", C.POINTER(kv_chunk_trace_t)), ("trace_cap", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 class kv_pipe_stats_t(C.Structure):
@@ -99,7 +105,7 @@ class kv_pipe_stats_t(C.Structure):
                 ("n_chunks", C.c_uint32), ("n_spans", C.c_uint32), ("max_in_flight", C.c_uint32),
                 ("group_seconds", C.c_double * 2),
                 ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4),
-                ("lba_seq_breaks", C.c_uint32), ("reserved", C.c_uint32),
+                ("lba_seq_breaks", C.c_uint32), ("n_traced", C.c_uint32),
                 ("host_copy_wait_s", C.c_double), ("harvest_wait_s", C.c_double)]
 
 
@@ -165,7 +171,8 @@ def lib() -> C.CDLL:
             getattr(L, name)
         # the ctypes mirrors must have the library's own struct sizes
         for which, t in enumerate((kv_plan_desc_t, kv_plan_info_t, kv_extent_t, kv_cmd_t, kv_view_t, kv_attn_args_t,
-                                   kv_pipe_opts_t, kv_pipe_stats_t, kv_append_stats_t, kv_adapt_t)):
+                                   kv_pipe_opts_t, kv_pipe_stats_t, kv_append_stats_t, kv_adapt_t,
+                                   kv_chunk_trace_t)):
             if L.kv_abi_sizeof(which) != C.sizeof(t):
                 raise RuntimeError(f"{t.__name__}: binding has {C.sizeof(t)} bytes, library {L.kv_abi_sizeof(which)}")
         _lib = L
@@ -400,10 +407,11 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
                     copy_streams: int = 0, d2h_mode: int = KV_COPY_AUTO, h2d_mode: int = KV_COPY_AUTO,
                     serialize: bool = False, attn_from_extent: bool = False,
                     order_pagecache: int = KV_ORDER_CROSS, order_direct: int = KV_ORDER_CROSS,
-                    max_cmd_bytes: int = 0, stream=None) -> kv_pipe_stats_t:
+                    max_cmd_bytes: int = 0, stream=None, trace_cap: int = 0) -> kv_pipe_stats_t:
     """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array.
     stream: the stream the view's buffers were produced on (default: PyTorch's current stream); the library
-    orders its own streams after it."""
+    orders its own streams after it.  trace_cap > 0: the returned stats carry `.trace`, the list of the first
+    trace_cap chunk commands as kv_chunk_trace_t."""
     def host(buf):
         if buf is None:
             return None, 0
@@ -422,12 +430,19 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
     opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0)
                           | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0), copy_streams,
                           d2h_mode, h2d_mode, order_pagecache, order_direct, max_cmd_bytes, _caller_stream(stream))
+    trace = (kv_chunk_trace_t * trace_cap)() if trace_cap > 0 else None
+    if trace is not None:
+        opts.trace = C.cast(trace, C.POINTER(kv_chunk_trace_t))
+        opts.trace_cap = trace_cap
     st = kv_pipe_stats_t()
     rc = lib().kv_pipeline_run(plan.handle, direction, layer_begin, layer_end, view.ref(), rp, rb, pp, pb,
                                chunk_tokens, depth, C.byref(attn) if attn is not None else None, C.byref(opts),
                                C.byref(st))
     del keep
     _check(rc, "kv_pipeline_run")
+    if trace is not None:
+        st.trace = [trace[i] for i in range(st.n_traced)]
+        st._trace_buf = trace
     return st
 
 

@@ -621,7 +621,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const size_t N = chunks.size();
     std::vector<unsigned> slot_used(n_slots, 0u);  // copy streams that carried the slot's last span
     size_t n_waited = 0;  // chunks [0, n_waited) are known complete
-    size_t n_issued = 0;  // offload: chunks [0, n_issued) have been issued
+    size_t n_issued = 0;  // chunks [0, n_issued) have been issued
     uint32_t max_in_flight = 0;
     int err = KV_OK;
 
@@ -631,6 +631,24 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     auto note_issue = [&](size_t c) {
         const int g = spans[chunks[c].span].path == KV_PATH_PAGECACHE ? 0 : 1;
         if (group_t0[g] < 0) group_t0[g] = now_s();
+    };
+    // optional per-command record: what was moved, when it was queued, when its completion was harvested
+    kv_chunk_trace_t *const trace = opts ? opts->trace : nullptr;
+    const size_t trace_cap = trace ? (size_t)opts->trace_cap : 0;
+    size_t n_traced = 0;
+    auto trace_issue = [&](size_t c) {
+        if (c >= trace_cap) return;
+        const Chunk &ch = chunks[c];
+        kv_chunk_trace_t &t = trace[c];
+        t.host_off = ch.host_off;
+        t.bytes = ch.bytes;
+        t.layer = (uint16_t)ch.layer;
+        t.kind = (uint8_t)ch.kind;
+        t.path = (uint8_t)spans[ch.span].path;
+        t.reserved = 0;
+        t.t_issue_s = now_s();
+        t.t_done_s = -1.0;
+        n_traced = c + 1;
     };
     auto host_ptr = [&](const Chunk &ch) -> char * {
         return (spans[ch.span].path == KV_PATH_DIRECT ? (char *)lba_region : (char *)pageable) + ch.host_off;
@@ -668,6 +686,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 fan_out(n_waited, host_ptr(chunks[n_waited]), bounce_ptr(n_waited), chunks[n_waited].bytes);
             for (int g = 0; g < 2; ++g)
                 if ((long long)n_waited == group_last[g]) group_t1[g] = now_s();
+            if (n_waited < trace_cap) trace[n_waited].t_done_s = now_s();
             ++n_waited;
         }
         return KV_OK;
@@ -755,6 +774,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 KV_HIP_BRK(issue_copy(bounce_ptr(c), img + ch.stage_off, ch.bytes, true, st, e.ev));
                 e.pending.store(1, std::memory_order_release);
             }
+            trace_issue(c);
             n_issued = c + 1;
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(c + 1 - n_waited));
             if (serialize) {  // every stage to completion before the next starts
@@ -807,6 +827,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 host_wait_s += spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st, e.ev));
             }
+            trace_issue(ci);
+            n_issued = ci + 1;
             max_in_flight = std::max<uint32_t>(max_in_flight, (uint32_t)(ci + 1 - n_waited));
             if (serialize && (err = harvest_until(ci + 1)) != KV_OK) break;
             if (stats) {
@@ -891,14 +913,12 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (ek != hipSuccess) e1 = ek;
     }
     hipError_t e2 = hipStreamSynchronize(q->s_compute);
-    if (offload_dir) {
-        // every issued transfer has landed: harvest the rest, which starts their memcpy hops (after an error the
-        // events may not all be usable: the hops of what was issued are started directly)
-        if (err != KV_OK || harvest_until(n_issued) != KV_OK) {
-            for (; n_waited < n_issued; ++n_waited)
-                if (spans[chunks[n_waited].span].path == KV_PATH_PAGECACHE)
-                    fan_out(n_waited, host_ptr(chunks[n_waited]), bounce_ptr(n_waited), chunks[n_waited].bytes);
-        }
+    // every issued transfer has landed: harvest the rest (offload: this starts their memcpy hops; after an error
+    // the events may not all be usable, and the hops of what was issued are started directly)
+    if (err != KV_OK || harvest_until(n_issued) != KV_OK) {
+        for (; offload_dir && n_waited < n_issued; ++n_waited)
+            if (spans[chunks[n_waited].span].path == KV_PATH_PAGECACHE)
+                fan_out(n_waited, host_ptr(chunks[n_waited]), bounce_ptr(n_waited), chunks[n_waited].bytes);
     }
     for (auto &e : q->ring) spin_until_zero(e.pending);
     if (err == KV_OK && (e1 != hipSuccess || e2 != hipSuccess)) {
@@ -914,6 +934,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         stats->lba_seq_breaks = sched.lba_seq_breaks;
         stats->host_copy_wait_s = host_wait_s;
         stats->harvest_wait_s = harvest_wait_s;
+        stats->n_traced = (uint32_t)n_traced;
         if (time_kernels && err == KV_OK) {
             for (size_t i = 0; i < timing_kind.size(); ++i) {
                 float ms = 0.f;

@@ -445,6 +445,7 @@ extern "C" size_t kv_abi_sizeof(int which)
     case 7: return sizeof(kv_pipe_stats_t);
     case 8: return sizeof(kv_append_stats_t);
     case 9: return sizeof(kv_adapt_t);
+    case 10: return sizeof(kv_chunk_trace_t);
     default: return 0;
     }
 }
@@ -464,4 +465,4 @@ extern "C" const char *kv_strerror(int code)
     }
 }
 
-extern "C" int kv_abi_version(void) { return 3; }
+extern "C" int kv_abi_version(void) { return 4; }

@@ -403,6 +403,45 @@ def test_pipeline_offload_reload(case, span_chunks, depth, copy_streams, d2h, h2
     _check_restored(case, k_new, v_new, range(cfg.n_layers))
 
 
+@pytest.mark.parametrize("depth", [1, 3])
+def test_pipeline_chunk_trace_shows_commands_and_depth_rule(case, depth):
+    """The per-command record of a run: the commands are exactly those of Eq. 7-11 for every tensor (and sequence)
+    in tensor-id order, as the checker computes them, and the queue-depth rule of Sec. IV-B "Data Flow" holds on the
+    issuing thread's clock: command c is issued only after command c - depth was harvested."""
+    from oracle import kv_oracle as o
+    cfg, r = case.cfg, case.ref
+    region = pinned_bytes(r.region_bytes, 0)
+    arena = np.zeros(max(r.pageable_bytes, 1), dtype=np.uint8)
+    nseq = len(case.lens) if r.per_seq else 1
+    want = []
+    for n in range(2 * cfg.n_layers):
+        for b in range(nseq):
+            rc, slba, req = o.token_range(r, n, b, 0, r.cap[b])
+            assert rc == o.OK
+            req = -(-req // r.lba_size) * r.lba_size           # the range reaches the extent tail: padded to a sector
+            for c_slba, nlb, _ in o.chunk_cmds(slba, req, cfg.chunk_tokens * r.row_bytes, r.lba_size):
+                want.append((n // 2, n % 2, int(r.path[n]), c_slba * r.lba_size, (nlb + 1) * r.lba_size))
+    k_new, v_new = case.blank_like_source()
+    for direction, view in ((kv.KV_DIR_OFFLOAD, case.view), (kv.KV_DIR_RELOAD, case.make_view(k_new, v_new))):
+        st = kv.kv_pipeline_run(case.plan, direction, 0, cfg.n_layers, view, region, arena, depth=depth,
+                                trace_cap=len(want) + 8)
+        tr = st.trace
+        assert st.n_traced == st.n_chunks == len(want)
+        # the checker's path codes are 0 direct / 1 page-cache; the library's constants are compared by meaning
+        got = [(t.layer, t.kind, 0 if t.path == kv.KV_PATH_DIRECT else 1, t.host_off, t.bytes) for t in tr]
+        assert got == want
+        for c, t in enumerate(tr):
+            assert 0.0 <= t.t_issue_s <= t.t_done_s <= st.wall_s
+            if c > 0:
+                assert tr[c - 1].t_issue_s <= t.t_issue_s and tr[c - 1].t_done_s <= t.t_done_s   # harvested in issue order
+            if c >= depth:
+                assert tr[c - depth].t_done_s <= t.t_issue_s
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+    # a record shorter than the run keeps the first entries only
+    st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=2, trace_cap=3)
+    assert st.n_traced == min(3, st.n_chunks) and [(t.host_off, t.bytes) for t in st.trace] == [w[3:] for w in want[:st.n_traced]]
+
+
 def test_pipeline_serialized_reference_run(case):
     """The no-overlap reference of the overlap fraction (every stage to completion before the next): same bytes,
     same reload, same attention, one command in flight."""

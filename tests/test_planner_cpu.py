@@ -34,7 +34,7 @@ def test_header_symbols_exported():
     lib = kv.lib()
     for name in declared:
         assert hasattr(lib, name)
-    assert lib.kv_abi_version() == 3
+    assert lib.kv_abi_version() == 4
     assert lib.kv_abi_sizeof(7) == kv.C.sizeof(kv.kv_pipe_stats_t) and lib.kv_abi_sizeof(99) == 0
 
 
