@@ -156,8 +156,8 @@ typedef struct kv_attn_args {
 #define KV_PIPE_SERIALIZE 2u    /* run every stage (kernel, chunk transfer, host copy) to completion before
                                    the next starts: the no-overlap reference for the overlap fraction */
 
-#define KV_COPY_AUTO 0   /* the faster of the two as measured: H2D hipMemcpyAsync; D2H hipMemcpyAsync for commands
-                            of >= 8 MiB, or >= 2 MiB at depth >= 4, else the copy kernel */
+#define KV_COPY_AUTO 0   /* the faster of the two as measured: H2D the copy kernel; D2H the copy kernel for commands
+                            below 1 MiB, hipMemcpyAsync from 1 MiB on */
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 
@@ -165,6 +165,10 @@ typedef struct kv_attn_args {
                                        attention reads the staged extent images directly (extent order is a
                                        strided [B,H,S,D] view) and nothing is unpacked: the view's K/V buffers
                                        are neither read nor written */
+#define KV_PIPE_NO_PACING 8u /* queue every command as soon as the depth rule allows.  By default consecutive
+                                commands are spaced by one command's own link time (at the best rate this plan's
+                                pipeline has sustained so far in that direction), which keeps commands that share
+                                the link from finishing together and leaving it idle while all are issued again */
 
 #define KV_ORDER_CROSS 0 /* per layer all of K's commands, then V's: V's storage-side hop overlaps K's transfers */
 #define KV_ORDER_INTRA 1 /* K's and V's commands alternate: both tensors' storage-side hops run side by side */
@@ -191,8 +195,7 @@ typedef struct kv_pipe_opts {
     int32_t host_workers; /* threads for the page-cache path's memcpy hop; 0 = default (8) */
     uint32_t flags;       /* KV_PIPE_* */
     int32_t copy_streams; /* streams the chunk commands rotate over, 1..4; 0 = default (3 for the copy kernel,
-                             4 for hipMemcpyAsync);
-                             never more than depth */
+                             4 for hipMemcpyAsync); never more than depth */
     int32_t d2h_mode;     /* KV_COPY_* for offload transfers */
     int32_t h2d_mode;     /* KV_COPY_* for reload transfers */
     int32_t order_pagecache; /* KV_ORDER_* for page-cache-path layers (the two overlap strategies of Sec. IV-C) */
@@ -201,8 +204,9 @@ typedef struct kv_pipe_opts {
                                 align_down(max_cmd_bytes, sector) moves as several commands of at most that
                                 size (Eq. 8-11 on the chunk), each counted against depth */
     void *caller_stream;     /* hipStream_t on which the caller produced (or still reads) the view's buffers, the
-                                queries and the block table; NULL = the default stream.  The library's own streams
-                                are ordered after everything queued on it when the call is entered */
+                                queries and the block table; NULL = the default stream.  The call's kernels are
+                                launched on it, behind everything queued there; the copies on the library's own
+                                streams follow them through events */
     kv_chunk_trace_t *trace; /* host, nullable: filled with the first trace_cap chunk commands of the call (the
                                 queue-depth rule of Sec. IV-B "Data Flow" can be read off it: command c is issued
                                 only after command c - depth was harvested); kv_pipe_stats_t.n_traced says how many */
@@ -228,6 +232,8 @@ typedef struct kv_pipe_stats {
     double host_copy_wait_s;  /* time the issuing thread waited for the page-cache path's memcpy hop (a bounce slot
                                  still being copied out of, or not yet filled): 0 when that hop keeps ahead of the link */
     double harvest_wait_s;    /* time the issuing thread waited for the oldest command's completion */
+    double pace_GBps;         /* the rate the issue pacing of this direction works from after this call: the best
+                                 sustained transfer rate seen so far (0 = none yet) */
 } kv_pipe_stats_t;
 
 /* ------------------------------------------------------------------------------------------ */
@@ -391,14 +397,14 @@ int kv_decode_attn_static(const kv_plan_t *plan, const kv_view_t *kv, int layer,
  * lba_region: pinned host memory (hipHostMalloc), region_bytes >= region_bytes_needed if any
  * direct-path layer is in range; pageable: ordinary host memory, pageable_bytes >=
  * pageable_bytes_needed if any page-cache-path layer is in range.  chunk_tokens 0 = the plan's.
- * The library owns its streams, events, staging slots, bounce ring and worker threads (created on
+ * The library owns its copy streams, events, staging slots, bounce ring and worker threads (created on
  * first use per plan, freed by kv_plan_destroy).  Calls on one plan must not overlap.
- * Stream order: the kernels and copies run on the library's streams.  On entry these are ordered after all
- * work already queued on opts->caller_stream (the default stream when opts or the field is NULL), so KV rows,
- * queries and block tables written by kernels on that stream are complete before the first pack or attention
- * launch reads them, and kernels still reading the view finish before an unpack overwrites it.  Work on any
- * other stream must be complete (or ordered before caller_stream) when the call is made.  The call returns
- * after its last kernel and copy have finished, so results are visible to every stream afterwards.
+ * Stream order: the copies run on the library's streams, the kernels on opts->caller_stream (the default stream
+ * when opts or the field is NULL), behind all work already queued there: KV rows, queries and block tables
+ * written by kernels on that stream are complete before the first pack or attention launch reads them, and
+ * kernels still reading the view finish before an unpack overwrites it.  Work on any other stream must be
+ * complete (or ordered before caller_stream) when the call is made.  The call returns after its last kernel and
+ * copy have finished (caller_stream is synchronised), so results are visible to every stream afterwards.
  * stats: host, may be NULL.
  */
 int kv_pipeline_run(kv_plan_t *plan, int dir, int layer_begin, int layer_end, const kv_view_t *view,
@@ -421,7 +427,7 @@ int kv_pipeline_run(kv_plan_t *plan, int dir, int layer_begin, int layer_end, co
  * names another lba_region or pageable base address than the one the images were taken from; they assume that
  * only this library writes the extents in between.
  * caller_stream: hipStream_t on which the new rows of the view were produced (NULL = the default stream); the
- * pack of the rows is ordered after everything queued on it at entry.
+ * pack of the rows and their transfer are queued on it, behind everything already there.
  */
 typedef struct kv_append_stats {
     uint32_t n_cmds;         /* write commands (one per tensor and sequence) */

@@ -29,6 +29,7 @@ KV_KERNEL_PACK, KV_KERNEL_UNPACK, KV_KERNEL_ATTN_PARTIAL, KV_KERNEL_ATTN_COMBINE
 KV_PIPE_TIME_KERNELS = 1
 KV_PIPE_SERIALIZE = 2
 KV_PIPE_ATTN_FROM_EXTENT = 4
+KV_PIPE_NO_PACING = 8
 KV_ATTN_SCRATCH_BYTES = 8 << 20
 KV_COPY_AUTO, KV_COPY_MEMCPY, KV_COPY_KERNEL = 0, 1, 2
 KV_ORDER_CROSS, KV_ORDER_INTRA = 0, 1
@@ -106,7 +107,7 @@ class kv_pipe_stats_t(C.Structure):
                 ("group_seconds", C.c_double * 2),
                 ("kernel_launches", C.c_uint32 * 4), ("kernel_ms", C.c_float * 4),
                 ("lba_seq_breaks", C.c_uint32), ("n_traced", C.c_uint32),
-                ("host_copy_wait_s", C.c_double), ("harvest_wait_s", C.c_double)]
+                ("host_copy_wait_s", C.c_double), ("harvest_wait_s", C.c_double), ("pace_GBps", C.c_double)]
 
 
 class kv_adapt_t(C.Structure):
@@ -407,10 +408,10 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
                     copy_streams: int = 0, d2h_mode: int = KV_COPY_AUTO, h2d_mode: int = KV_COPY_AUTO,
                     serialize: bool = False, attn_from_extent: bool = False,
                     order_pagecache: int = KV_ORDER_CROSS, order_direct: int = KV_ORDER_CROSS,
-                    max_cmd_bytes: int = 0, stream=None, trace_cap: int = 0) -> kv_pipe_stats_t:
+                    max_cmd_bytes: int = 0, stream=None, trace_cap: int = 0, pacing: bool = True) -> kv_pipe_stats_t:
     """lba_region: pinned torch uint8 CPU tensor; pageable: ordinary torch uint8 CPU tensor or NumPy array.
-    stream: the stream the view's buffers were produced on (default: PyTorch's current stream); the library
-    orders its own streams after it.  trace_cap > 0: the returned stats carry `.trace`, the list of the first
+    stream: the stream the view's buffers were produced on (default: PyTorch's current stream); the call's
+    kernels are queued on it.  trace_cap > 0: the returned stats carry `.trace`, the list of the first
     trace_cap chunk commands as kv_chunk_trace_t."""
     def host(buf):
         if buf is None:
@@ -428,7 +429,7 @@ def kv_pipeline_run(plan: Plan, direction: int, layer_begin: int, layer_end: int
         attn = kv_attn_args_t(qa, oa, out_dtype, n_splits)
         keep = (qa, oa)
     opts = kv_pipe_opts_t(span_chunks, host_workers, (KV_PIPE_TIME_KERNELS if time_kernels else 0) | (KV_PIPE_SERIALIZE if serialize else 0)
-                          | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0), copy_streams,
+                          | (KV_PIPE_ATTN_FROM_EXTENT if attn_from_extent else 0) | (0 if pacing else KV_PIPE_NO_PACING), copy_streams,
                           d2h_mode, h2d_mode, order_pagecache, order_direct, max_cmd_bytes, _caller_stream(stream))
     trace = (kv_chunk_trace_t * trace_cap)() if trace_cap > 0 else None
     if trace is not None:

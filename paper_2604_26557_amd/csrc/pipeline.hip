@@ -10,14 +10,14 @@
 //    256 MiB, or several small layers of one path together, by default (HBM is large, so staging whole
 //    extents costs nothing and the pack / unpack launches are big enough to run at HBM speed), or every
 //    `span_chunks` chunks of one tensor on request.
-// Streams: one for kernels and up to four for copies (chunk c goes to copy stream c mod n, so the
+// Streams: the caller's own for kernels and up to four for copies (chunk c goes to copy stream c mod n, so the
 // start-up and tail of one transfer hide behind the next); events order pack -> D2H and
 // H2D -> unpack -> attention and guard staging-slot reuse.  All streams keep the default priority.
-// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): commands of up to 1 MiB move
-// fastest, in both directions, as this file's own copy kernel (three streams D2H, two H2D; its completion
-// event rides on the dispatch: the runtime's per-command cost dominates copies of a few hundred KiB);
-// larger ones as hipMemcpyAsync over up to four streams (D2H from 2 MiB at depth >= 4, else from 8 MiB).
-// Both engines are options.
+// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D commands of every size, and D2H
+// commands below 1 MiB, move fastest as this file's own copy kernel over three streams (its completion event
+// rides on the dispatch: the runtime's per-command cost dominates copies of a few hundred KiB); D2H commands
+// from 1 MiB on as hipMemcpyAsync over up to four streams.  Both engines are options.  Commands are issued
+// no closer together than one command's own link time, which keeps them from finishing in lockstep.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
@@ -199,7 +199,7 @@ struct Entry {
 
 struct kv_pipeline {
     int device = 0;
-    hipStream_t s_compute = nullptr;
+    hipStream_t s_compute = nullptr;  // the caller's stream of the running call (not owned): kernels are launched on it
     hipStream_t s_copy[kMaxCopyStreams] = {nullptr, nullptr, nullptr, nullptr};
     void *staging = nullptr;
     size_t staging_bytes = 0;
@@ -221,27 +221,29 @@ struct kv_pipeline {
     std::vector<char> tail_img;
     std::vector<int64_t> tail_sector;
     const void *tail_region = nullptr, *tail_pageable = nullptr;  // host buffers the images were taken from
-    hipEvent_t ev_entry = nullptr;  // orders the library's streams after the caller's stream at call entry
+    // Issue pacing (see kv_pipeline_run): the best transfer rate seen so far per direction (0 offload, 1 reload),
+    // bytes per second; 0 = nothing seen yet
+    double pace_rate[2] = {0.0, 0.0};
+    bool link_measured = false;
+    int pace_above[2] = {0, 0};        // consecutive windows that ran above pace_rate, and the lowest of them
+    double pace_low[2] = {0.0, 0.0};
 
     ~kv_pipeline()
     {
         workers.stop();
         (void)hipSetDevice(device);
         for (auto st : s_copy) if (st) (void)hipStreamSynchronize(st);
-        if (s_compute) (void)hipStreamSynchronize(s_compute);
         for (auto e : ev_ready) (void)hipEventDestroy(e);
         for (auto e : ev_free) (void)hipEventDestroy(e);
         for (auto e : ev_done) (void)hipEventDestroy(e);
         for (auto &e : ring) if (e.ev) (void)hipEventDestroy(e.ev);
         for (auto e : timing) (void)hipEventDestroy(e);
-        if (ev_entry) (void)hipEventDestroy(ev_entry);
         if (staging) (void)hipFree(staging);
         if (bounce) (void)hipHostFree(bounce);
         if (append_host) (void)hipHostFree(append_host);
         if (seq_off_dev) (void)hipFree(seq_off_dev);
         if (attn_ws) (void)hipFree(attn_ws);
         for (auto st : s_copy) if (st) (void)hipStreamDestroy(st);
-        if (s_compute) (void)hipStreamDestroy(s_compute);
     }
 };
 
@@ -257,15 +259,52 @@ int ensure_events(std::vector<hipEvent_t> &v, size_t n, unsigned flags)
     return KV_OK;
 }
 
+// The host link's transfer rate in both directions, for the issue pacing: best of five timed copies of up to
+// 64 MiB between a pinned buffer of its own and the staging memory (nothing of the caller's is touched).  Done once
+// per pipeline (about 12 ms); a rate that cannot be measured stays 0 and the pacing then works from what the run itself shows.
+int measure_link_rates(kv_pipeline *q)
+{
+    const size_t bytes = std::min<size_t>(q->staging_bytes, 64u << 20);
+    if (bytes < (1u << 20)) return KV_OK;
+    void *pinned = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    q->link_measured = true;   // one attempt only
+    if (hipHostMalloc(&pinned, bytes, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return KV_OK; }
+    std::memset(pinned, 0, bytes);
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    for (int dir = 0; dir < 2 && e == hipSuccess; ++dir) {
+        for (int pass = 0; pass < 6 && e == hipSuccess; ++pass) {   // the first pass warms the path up
+            e = hipEventRecord(e0, q->s_copy[0]);
+            if (e == hipSuccess)
+                e = dir == 0 ? hipMemcpyAsync(pinned, q->staging, bytes, hipMemcpyDeviceToHost, q->s_copy[0])
+                             : hipMemcpyAsync(q->staging, pinned, bytes, hipMemcpyHostToDevice, q->s_copy[0]);
+            if (e == hipSuccess) e = hipEventRecord(e1, q->s_copy[0]);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+            float ms = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+            if (e == hipSuccess && pass > 0 && ms > 0.f) q->pace_rate[dir] = std::max(q->pace_rate[dir], (double)bytes / (ms * 1e-3));
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipHostFree(pinned);
+    if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
+    return KV_OK;
+}
+
 int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, size_t chunk_bytes_max, bool need_bounce,
                     int n_workers, size_t attn_ws_bytes, size_t n_timing)
 {
     if (!p->pipe) {
         p->pipe = new kv_pipeline();
         KV_HIP(hipGetDevice(&p->pipe->device));
-        KV_HIP(hipStreamCreateWithFlags(&p->pipe->s_compute, hipStreamNonBlocking));
+        // The runtime maps streams onto a few hardware queues (four per process by default; a stream created when all
+        // exist shares the least used one), and two streams on one queue run their commands one after the other: a
+        // copy stream that shared its queue with the kernel stream made every third 512 KiB command 8 us late.  So
+        // the library has no kernel stream of its own: kernels go to the caller's stream, which has its queue
+        // already, and the three copy streams that small commands rotate over are created first.
         for (auto &st : p->pipe->s_copy) KV_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
-        KV_HIP(hipEventCreateWithFlags(&p->pipe->ev_entry, hipEventDisableTiming));
     }
     kv_pipeline *q = p->pipe;
     const size_t need = n_slots * slot_bytes;
@@ -303,6 +342,10 @@ int ensure_pipeline(kv_plan *p, size_t n_slots, size_t slot_bytes, int depth, si
     rc = ensure_events(q->timing, n_timing, hipEventDefault);
     if (rc) return rc;
     if (need_bounce) q->workers.start(n_workers);
+    if (!q->link_measured && depth >= 2) {
+        rc = measure_link_rates(q);
+        if (rc) return rc;
+    }
     return KV_OK;
 }
 
@@ -445,13 +488,12 @@ int build_schedule(const kv_plan *p, int layer_begin, int layer_end, uint64_t C,
     return KV_OK;
 }
 
-// The kernels of a call read (or overwrite) buffers the caller produced on its own stream: order the kernel
-// stream after everything queued there so far.  The copy streams only follow the kernel stream (offload) or
-// touch library-owned staging (reload), so this one edge is enough.
+// The kernels of a call read (or overwrite) buffers the caller produced on its own stream, so they are launched on
+// that stream: they follow everything queued there so far.  The copy streams only follow the kernels (offload) or
+// touch library-owned staging (reload), through events.
 int order_after_caller(kv_pipeline *q, void *caller_stream)
 {
-    KV_HIP(hipEventRecord(q->ev_entry, (hipStream_t)caller_stream));
-    KV_HIP(hipStreamWaitEvent(q->s_compute, q->ev_entry, 0));
+    q->s_compute = (hipStream_t)caller_stream;
     return KV_OK;
 }
 
@@ -507,10 +549,12 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     const int d2h_mode = opts ? opts->d2h_mode : KV_COPY_AUTO, h2d_mode = opts ? opts->h2d_mode : KV_COPY_AUTO;
     if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
         return KV_EINVAL;
-    // Engine defaults by measurement: H2D as the copy kernel over two streams for commands of up to 1 MiB, as
-    // hipMemcpyAsync over four streams above; D2H as hipMemcpyAsync over up to four streams for commands of
-    // 8 MiB and more, and of 2 MiB and more when four may be in flight; as the copy kernel over three streams
-    // otherwise.
+    // Engine defaults by measurement inside the paced pipeline (8B shape at 4K / 32K, ragged paged batch, Gemma
+    // shape): H2D is fastest as the copy kernel over three streams at every command size (32K shape: reload +
+    // attention 55.6-56.2 GB/s against 53.5-54.1 with hipMemcpyAsync; Gemma shape 57.2 against 56.0-56.9); D2H as
+    // the copy kernel over three streams below 1 MiB (512 KiB commands: 51 against 42 GB/s), as hipMemcpyAsync
+    // over up to four streams from 1 MiB on (ragged batch 52.3 against 51.1; larger commands 1-2 GB/s apart): there
+    // the copy kernel's loads queue behind the pack kernel's, and the SDMA engines are not in that queue.
     uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
     uint64_t cmd_limit = UINT64_MAX;  // Eq. 7 on the caller's transfer-size limit
     if (opts && opts->max_cmd_bytes) {
@@ -518,15 +562,14 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (cmd_limit == 0) return KV_EINVAL;
         cmd_bytes = std::min(cmd_bytes, cmd_limit);
     }
-    const bool d2h_big = cmd_bytes >= (8ull << 20) || (cmd_bytes >= (2ull << 20) && depth >= 4);
-    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && !d2h_big);
-    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL || (h2d_mode == KV_COPY_AUTO && cmd_bytes <= (1ull << 20));
+    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && cmd_bytes < (1ull << 20));
+    const bool h2d_kernel = h2d_mode != KV_COPY_MEMCPY;
     const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
     const int order_direct = opts ? opts->order_direct : KV_ORDER_CROSS;
     if ((order_pc != KV_ORDER_CROSS && order_pc != KV_ORDER_INTRA) ||
         (order_direct != KV_ORDER_CROSS && order_direct != KV_ORDER_INTRA))
         return KV_EINVAL;
-    if (ns == 0) ns = offload_dir ? (d2h_kernel ? 3 : 4) : (h2d_kernel ? 2 : 4);
+    if (ns == 0) ns = (offload_dir ? d2h_kernel : h2d_kernel) ? 3 : 4;
     ns = std::min(ns, depth);
     if (stats) std::memset(stats, 0, sizeof(*stats));
     if (layer_begin == layer_end) return KV_OK;
@@ -672,15 +715,64 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         q->workers.push(tasks, n_tasks);
     };
 
+    // Issue pacing.  Commands that are queued back to back share the link, finish together and leave it idle
+    // while all of them are issued again (at 512 KiB and depth 3: 45 of 56.5 GB/s).  Spaced by one command's own
+    // link time they stay staggered: one completes while the others still move, and its successor is on its way
+    // before they end (54 GB/s; the spacing has to be right within a few percent: 0.97 of the link time gives 52,
+    // 1.06 gives 52.5, 0.85 gives 47).  The spacing is the previous command's bytes over the link rate measured when
+    // the pipeline was created, or over the best rate a run has sustained since, if that is higher (measured
+    // between completions the thread really waited for, over windows of several queue depths): the rate only
+    // ratchets upward, so pacing never holds the commands below what the link has already shown.  Both copy
+    // engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
+    const bool paced = depth >= 2 && !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING));
+    const int pace_dir = offload_dir ? 0 : 1;
+    constexpr double kPaceHeadroom = 1.02;
+    const size_t pace_window = std::max<size_t>(16, 8 * (size_t)depth);
+    double pace_last_issue = -1.0, pace_last_bytes = 0.0;
+    double win_t0 = -1.0, win_bytes = 0.0;
+    size_t win_n = 0;
+    auto pace_issue = [&](uint64_t bytes) {   // call right before a command is queued
+        const double rate = q->pace_rate[pace_dir];
+        if (paced && rate > 0.0 && pace_last_issue >= 0.0) {
+            const double due = pace_last_issue + pace_last_bytes / (kPaceHeadroom * rate);
+            while (now_s() < due) __builtin_ia32_pause();
+        }
+        pace_last_issue = now_s();
+        pace_last_bytes = (double)bytes;
+    };
+    auto pace_harvest = [&](uint64_t bytes, bool waited) {   // call when a completion is harvested
+        if (!paced) return;
+        if (win_t0 >= 0.0) { win_bytes += (double)bytes; ++win_n; }
+        if (!waited) return;                      // only a completion the thread waited for has an exact time
+        const double t = now_s();
+        if (win_t0 >= 0.0 && win_n >= pace_window && t > win_t0) {
+            // a window's rate carries a percent or two of timing noise: the rate moves up only after three windows
+            // in a row came out above it, and then to the lowest of the three
+            const double seen = win_bytes / (t - win_t0);
+            double &rate = q->pace_rate[pace_dir];
+            if (seen > rate) {
+                q->pace_low[pace_dir] = q->pace_above[pace_dir] == 0 ? seen : std::min(q->pace_low[pace_dir], seen);
+                if (++q->pace_above[pace_dir] >= 3) { rate = q->pace_low[pace_dir]; q->pace_above[pace_dir] = 0; }
+            } else {
+                q->pace_above[pace_dir] = 0;
+            }
+            win_t0 = -1.0;
+        }
+        if (win_t0 < 0.0) { win_t0 = t; win_bytes = 0.0; win_n = 0; }
+    };
+
     // Chunk c owns ring entry c % NB.  Transfers are harvested in issue order; n_waited counts them.
     double host_wait_s = 0.0, harvest_wait_s = 0.0;
     auto harvest_until = [&](size_t upto) -> int {  // transfers of chunks [0, upto) are complete
         while (n_waited < upto) {
+            bool waited = false;
             if (hipEventQuery(q->ring[n_waited % NB].ev) != hipSuccess) {
                 const double t0 = now_s();
                 KV_HIP(hipEventSynchronize(q->ring[n_waited % NB].ev));
                 harvest_wait_s += now_s() - t0;
+                waited = true;
             }
+            pace_harvest(chunks[n_waited].bytes, waited);
             // offload, page-cache path: the chunk's bytes are in its bounce slot now; start the memcpy hop
             if (offload_dir && spans[chunks[n_waited].span].path == KV_PATH_PAGECACHE)
                 fan_out(n_waited, host_ptr(chunks[n_waited]), bounce_ptr(n_waited), chunks[n_waited].bytes);
@@ -766,6 +858,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 KV_HIP_BRK(hipStreamWaitEvent(st, q->ev_ready[slot], 0));
                 used |= 1u << s;
             }
+            pace_issue(ch.bytes);
             if (sp.path == KV_PATH_DIRECT) {
                 KV_HIP_BRK(issue_copy(host_ptr(ch), img + ch.stage_off, ch.bytes, true, st, e.ev));
             } else {
@@ -822,9 +915,11 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 used |= 1u << s;
             }
             if (sp.path == KV_PATH_DIRECT) {
+                pace_issue(ch.bytes);
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, host_ptr(ch), ch.bytes, false, st, e.ev));
             } else {
                 host_wait_s += spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
+                pace_issue(ch.bytes);
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st, e.ev));
             }
             trace_issue(ci);
@@ -935,6 +1030,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         stats->host_copy_wait_s = host_wait_s;
         stats->harvest_wait_s = harvest_wait_s;
         stats->n_traced = (uint32_t)n_traced;
+        stats->pace_GBps = q->pace_rate[pace_dir] / 1e9;
         if (time_kernels && err == KV_OK) {
             for (size_t i = 0; i < timing_kind.size(); ++i) {
                 float ms = 0.f;
