@@ -26,10 +26,10 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # copy of known size in the same run.  Valid only for the kernel sources they were taken with: the hash below
 # covers the two kernel files, and a mismatch reports traffic as null.
 PMC_TRAFFIC = {"sha": "f663734213d3c082",
-               "llama8b_32k": {"kv_layout_kernel<pack>": 268501489, "kv_layout_kernel<unpack>": 268458776, "kv_attn_partial_kernel+kv_attn_combine_kernel": 135566734},
-               "llama8b_4k": {"kv_layout_kernel<pack>": 268551112, "kv_layout_kernel<unpack>": 268454181, "kv_attn_partial_kernel+kv_attn_combine_kernel": 18132873},
-               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282195672, "kv_layout_kernel<unpack>": 282060312, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142719609},
-               "gemma7b_mha_8k": {"kv_layout_kernel<pack>": 536934390, "kv_layout_kernel<unpack>": 536903830, "kv_attn_partial_kernel+kv_attn_combine_kernel": 539587232}}
+               "llama8b_32k": {"kv_layout_kernel<pack>": 268518990, "kv_layout_kernel<unpack>": 268454551, "kv_attn_partial_kernel+kv_attn_combine_kernel": 135563606},
+               "llama8b_4k": {"kv_layout_kernel<pack>": 268568476, "kv_layout_kernel<unpack>": 268452905, "kv_attn_partial_kernel+kv_attn_combine_kernel": 18133226},
+               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282205699, "kv_layout_kernel<unpack>": 282059040, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142720829},
+               "gemma7b_mha_8k": {"kv_layout_kernel<pack>": 536936288, "kv_layout_kernel<unpack>": 536903912, "kv_attn_partial_kernel+kv_attn_combine_kernel": 539580899}}
 
 
 def kernel_sources_hash() -> str:
