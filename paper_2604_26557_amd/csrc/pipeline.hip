@@ -553,8 +553,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // shape): H2D is fastest as the copy kernel over three streams at every command size (32K shape: reload +
     // attention 55.6-56.2 GB/s against 53.5-54.1 with hipMemcpyAsync; Gemma shape 57.2 against 56.0-56.9); D2H as
     // the copy kernel over three streams below 1 MiB (512 KiB commands: 51 against 42 GB/s), as hipMemcpyAsync
-    // over up to four streams from 1 MiB on (ragged batch 52.3 against 51.1; larger commands 1-2 GB/s apart): there
-    // the copy kernel's loads queue behind the pack kernel's, and the SDMA engines are not in that queue.
+    // over up to four streams from 1 MiB on (ragged batch 52.3 against 51.1; larger commands 1-2 GB/s apart; the
+    // runtime runs those D2H copies as a wide-grid kernel of its own, which holds up better next to a pack kernel).
     uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
     uint64_t cmd_limit = UINT64_MAX;  // Eq. 7 on the caller's transfer-size limit
     if (opts && opts->max_cmd_bytes) {
