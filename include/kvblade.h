@@ -157,7 +157,7 @@ typedef struct kv_attn_args {
                                    the next starts: the no-overlap reference for the overlap fraction */
 
 #define KV_COPY_AUTO 0   /* the faster of the two as measured: H2D the copy kernel; D2H the copy kernel for commands
-                            below 1 MiB, hipMemcpyAsync from 1 MiB on */
+                            below 2 MiB, hipMemcpyAsync from 2 MiB on */
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 
@@ -166,8 +166,8 @@ typedef struct kv_attn_args {
                                        strided [B,H,S,D] view) and nothing is unpacked: the view's K/V buffers
                                        are neither read nor written */
 #define KV_PIPE_NO_PACING 8u /* queue every command as soon as the depth rule allows.  By default consecutive
-                                commands are spaced by one command's own link time (at the best rate this plan's
-                                pipeline has sustained so far in that direction), which keeps commands that share
+                                commands are spaced by one command's own link time (at the link rate the library
+                                measured on first use, or the best rate a run has sustained since), which keeps commands that share
                                 the link from finishing together and leaving it idle while all are issued again */
 
 #define KV_ORDER_CROSS 0 /* per layer all of K's commands, then V's: V's storage-side hop overlaps K's transfers */

@@ -14,9 +14,9 @@
 // start-up and tail of one transfer hide behind the next); events order pack -> D2H and
 // H2D -> unpack -> attention and guard staging-slot reuse.  All streams keep the default priority.
 // Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D commands of every size, and D2H
-// commands below 1 MiB, move fastest as this file's own copy kernel over three streams (its completion event
+// commands below 2 MiB, move fastest as this file's own copy kernel over three streams (its completion event
 // rides on the dispatch: the runtime's per-command cost dominates copies of a few hundred KiB); D2H commands
-// from 1 MiB on as hipMemcpyAsync over up to four streams.  Both engines are options.  Commands are issued
+// from 2 MiB on as hipMemcpyAsync over up to four streams.  Both engines are options.  Commands are issued
 // no closer together than one command's own link time, which keeps them from finishing in lockstep.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
@@ -261,9 +261,22 @@ int ensure_events(std::vector<hipEvent_t> &v, size_t n, unsigned flags)
 
 // The host link's transfer rate in both directions, for the issue pacing: best of five timed copies of up to
 // 64 MiB between a pinned buffer of its own and the staging memory (nothing of the caller's is touched).  Done once
-// per pipeline (about 12 ms); a rate that cannot be measured stays 0 and the pacing then works from what the run itself shows.
+// per process and device (about 12 ms), by the first pipeline whose staging memory is large enough; a rate that
+// cannot be measured stays 0, and the pacing then works from what the run itself shows.
+std::mutex g_link_mu;
+double g_link_rate[64][2];   // per device, measured once per process
+bool g_link_known[64];
+
 int measure_link_rates(kv_pipeline *q)
 {
+    std::lock_guard<std::mutex> g(g_link_mu);
+    const int dev = q->device >= 0 && q->device < 64 ? q->device : 0;
+    if (g_link_known[dev]) {
+        q->pace_rate[0] = std::max(q->pace_rate[0], g_link_rate[dev][0]);
+        q->pace_rate[1] = std::max(q->pace_rate[1], g_link_rate[dev][1]);
+        q->link_measured = true;
+        return KV_OK;
+    }
     const size_t bytes = std::min<size_t>(q->staging_bytes, 64u << 20);
     if (bytes < (1u << 20)) return KV_OK;
     void *pinned = nullptr;
@@ -290,6 +303,11 @@ int measure_link_rates(kv_pipeline *q)
     if (e1) (void)hipEventDestroy(e1);
     (void)hipHostFree(pinned);
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
+    if (q->pace_rate[0] > 0.0 && q->pace_rate[1] > 0.0) {
+        g_link_rate[dev][0] = q->pace_rate[0];
+        g_link_rate[dev][1] = q->pace_rate[1];
+        g_link_known[dev] = true;
+    }
     return KV_OK;
 }
 
@@ -550,11 +568,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
         return KV_EINVAL;
     // Engine defaults by measurement inside the paced pipeline (8B shape at 4K / 32K, ragged paged batch, Gemma
-    // shape): H2D is fastest as the copy kernel over three streams at every command size (32K shape: reload +
-    // attention 55.6-56.2 GB/s against 53.5-54.1 with hipMemcpyAsync; Gemma shape 57.2 against 56.0-56.9); D2H as
-    // the copy kernel over three streams below 1 MiB (512 KiB commands: 51 against 42 GB/s), as hipMemcpyAsync
-    // over up to four streams from 1 MiB on (ragged batch 52.3 against 51.1; larger commands 1-2 GB/s apart; the
-    // runtime runs those D2H copies as a wide-grid kernel of its own, which holds up better next to a pack kernel).
+    // shape; three alternations per variant in one process): H2D is fastest as the copy kernel over three streams
+    // at every command size (32K shape: reload + attention 55.6-56.2 GB/s against 53.5-54.1 with hipMemcpyAsync;
+    // Gemma shape 57.2 against 56.0-56.9); D2H as the copy kernel over three streams below 2 MiB (512 KiB commands:
+    // 48 against 42 GB/s; 1 MiB: 52.9 steady against 50.7-53.4), as hipMemcpyAsync over up to four streams from
+    // 2 MiB on (2 MiB: 54.4-55.9 against 54.0-54.7; 8 MiB: 55.9-56.8 against 55.2-55.4; the runtime runs those
+    // copies as a kernel of its own).  Eight workgroups per command in both directions: 16, 32 and 64 lose
+    // 2, 4 and 7-14 GB/s on the reload side, where the unpack and attention kernels run next to the copies.
     uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
     uint64_t cmd_limit = UINT64_MAX;  // Eq. 7 on the caller's transfer-size limit
     if (opts && opts->max_cmd_bytes) {
@@ -562,7 +582,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (cmd_limit == 0) return KV_EINVAL;
         cmd_bytes = std::min(cmd_bytes, cmd_limit);
     }
-    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && cmd_bytes < (1ull << 20));
+    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && cmd_bytes < (2ull << 20));
     const bool h2d_kernel = h2d_mode != KV_COPY_MEMCPY;
     const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
     const int order_direct = opts ? opts->order_direct : KV_ORDER_CROSS;
