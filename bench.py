@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 PMC_TRAFFIC = {"sha": "f663734213d3c082",
                "llama8b_32k": {"kv_layout_kernel<pack>": 268518990, "kv_layout_kernel<unpack>": 268454551, "kv_attn_partial_kernel+kv_attn_combine_kernel": 135563606},
                "llama8b_4k": {"kv_layout_kernel<pack>": 268568476, "kv_layout_kernel<unpack>": 268452905, "kv_attn_partial_kernel+kv_attn_combine_kernel": 18133226},
-               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282205699, "kv_layout_kernel<unpack>": 282059040, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142720829},
+               "llama8b_ragged_paged": {"kv_layout_kernel<pack>": 282200486, "kv_layout_kernel<unpack>": 282059080, "kv_attn_partial_kernel+kv_attn_combine_kernel": 142723049},
                "gemma7b_mha_8k": {"kv_layout_kernel<pack>": 536936288, "kv_layout_kernel<unpack>": 536903912, "kv_attn_partial_kernel+kv_attn_combine_kernel": 539580899}}
 
 
