@@ -442,6 +442,26 @@ def test_pipeline_chunk_trace_shows_commands_and_depth_rule(case, depth):
     assert st.n_traced == min(3, st.n_chunks) and [(t.host_off, t.bytes) for t in st.trace] == [w[3:] for w in want[:st.n_traced]]
 
 
+def test_pipeline_without_issue_pacing(case):
+    """KV_PIPE_NO_PACING: every command is queued as soon as the depth rule allows; same bytes either way."""
+    cfg, r = case.cfg, case.ref
+    FILL = 0x3C
+    region = pinned_bytes(r.region_bytes, FILL)
+    arena = np.full(max(r.pageable_bytes, 1), FILL, dtype=np.uint8)
+    want_region, want_arena = case.expected_host(fill=FILL)
+    for pacing in (False, True):
+        region.fill_(FILL)
+        arena[:] = FILL
+        st = kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=3, pacing=pacing)
+        assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+        assert np.array_equal(arena[:r.pageable_bytes], want_arena[:r.pageable_bytes])
+        assert st.max_in_flight <= 3 and st.pace_GBps >= 0.0
+        k_new, v_new = case.blank_like_source()
+        kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, cfg.n_layers, case.make_view(k_new, v_new), region, arena,
+                           depth=3, pacing=pacing)
+        _check_restored(case, k_new, v_new, range(cfg.n_layers))
+
+
 def test_pipeline_serialized_reference_run(case):
     """The no-overlap reference of the overlap fraction (every stage to completion before the next): same bytes,
     same reload, same attention, one command in flight."""
