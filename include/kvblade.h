@@ -232,8 +232,8 @@ typedef struct kv_pipe_stats {
     double host_copy_wait_s;  /* time the issuing thread waited for the page-cache path's memcpy hop (a bounce slot
                                  still being copied out of, or not yet filled): 0 when that hop keeps ahead of the link */
     double harvest_wait_s;    /* time the issuing thread waited for the oldest command's completion */
-    double pace_GBps;         /* the rate the issue pacing of this direction works from after this call: the best
-                                 sustained transfer rate seen so far (0 = none yet) */
+    double pace_GBps;         /* the link rate the issue pacing of this direction works from after this call
+                                 (0 = none measured: commands are not paced) */
 } kv_pipe_stats_t;
 
 /* ------------------------------------------------------------------------------------------ */

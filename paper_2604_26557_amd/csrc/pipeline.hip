@@ -262,7 +262,7 @@ int ensure_events(std::vector<hipEvent_t> &v, size_t n, unsigned flags)
 // The host link's transfer rate in both directions, for the issue pacing: best of five timed copies of up to
 // 64 MiB between a pinned buffer of its own and the staging memory (nothing of the caller's is touched).  Done once
 // per process and device (about 12 ms), by the first pipeline whose staging memory is large enough; a rate that
-// cannot be measured stays 0, and the pacing then works from what the run itself shows.
+// cannot be measured stays 0, and that direction is then not paced.
 std::mutex g_link_mu;
 double g_link_rate[64][2];   // per device, measured once per process
 bool g_link_known[64];
@@ -740,11 +740,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // link time they stay staggered: one completes while the others still move, and its successor is on its way
     // before they end (54 GB/s; the spacing has to be right within a few percent: 0.97 of the link time gives 52,
     // 1.06 gives 52.5, 0.85 gives 47).  The spacing is the previous command's bytes over the link rate measured when
-    // the pipeline was created, or over the best rate a run has sustained since, if that is higher (measured
+    // the process first ran a pipeline, or over the best rate a run has sustained since, if that is higher (measured
     // between completions the thread really waited for, over windows of several queue depths): the rate only
     // ratchets upward, so pacing never holds the commands below what the link has already shown.  Both copy
     // engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
-    const bool paced = depth >= 2 && !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING));
+    // (without a measured link rate -- a pipeline whose staging memory is too small to measure one -- nothing is paced:
+    // a rate taken from the run's own first windows could be a stalled one and hold everything back)
+    const bool paced = depth >= 2 && !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)) && q->pace_rate[offload_dir ? 0 : 1] > 0.0;
     const int pace_dir = offload_dir ? 0 : 1;
     constexpr double kPaceHeadroom = 1.02;
     const size_t pace_window = std::max<size_t>(16, 8 * (size_t)depth);
