@@ -373,6 +373,44 @@ def test_decode_attention_long_splits_every_head_shape(D, G, paged):
             _attn_check(out, want)
 
 
+@pytest.mark.parametrize("bt", [1, 8, 12, 32, 48])
+def test_paged_source_other_block_sizes(bt):
+    """Paged pools whose blocks hold other than 16 token rows (a power of two below and above the 16-row tile, sizes
+    that are not powers of two, one row per block): pack, unpack, decode attention and a pipeline round trip against
+    the checker."""
+    torch.cuda.set_device(0)
+    H, G, D = 2, 4, 128
+    lens = [700, 33, 257]
+    cfg = W.KVConfig(f"paged_bt{bt}", 4200 + bt, 2, H, H * G, D, len(lens), W.F16 if bt % 2 else W.BF16, 512, 8, 2, W.PER_SEQ,
+                     W.PAGED, 0, len_range=(1, 2), block_tokens=bt)
+    case = Case(cfg, "cuda", lens=list(lens), raw=True)
+    r = case.ref
+    nbytes = r.n_blocks_tensor * r.lba_size
+    for layer, kind in ((0, 0), (1, 1)):
+        buf, dst = _guarded(nbytes)
+        kv.kv_offload_pack(case.plan, layer, kind, case.view, kv.KV_SEQ_ALL, 0, 0, dst)
+        torch.cuda.synchronize()
+        assert np.array_equal(dst.cpu().numpy(), case.expected_extent(layer, kind)) and _guards_intact(buf, nbytes)
+    region = pinned_bytes(r.region_bytes, 0x5A)
+    arena = np.full(max(r.pageable_bytes, 1), 0x5A, dtype=np.uint8)
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_OFFLOAD, 0, cfg.n_layers, case.view, region, arena, depth=2)
+    want_region, _ = case.expected_host(fill=0x5A)
+    assert np.array_equal(region.numpy()[:r.region_bytes], want_region[:r.region_bytes])
+    k_new, v_new = case.blank_like_source()
+    kv.kv_pipeline_run(case.plan, kv.KV_DIR_RELOAD, 0, cfg.n_layers, case.make_view(k_new, v_new), region, arena, depth=2)
+    _check_restored(case, k_new, v_new, range(cfg.n_layers))
+    # attention on values that are numbers (the raw bit patterns above include NaNs)
+    case = Case(cfg, "cuda", lens=list(lens))
+    q = W.query(cfg, 0, "cpu")
+    want = case.expected_attention(0, q)
+    for n_splits in (0, 3):
+        out = torch.full((len(lens), H * G, D), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(kv.kv_decode_attn_workspace(case.plan, n_splits, max(lens)), dtype=torch.uint8, device="cuda")
+        kv.kv_decode_attn(case.plan, case.view, 0, q.cuda(), out, kv.KV_OUT_F32, n_splits, ws)
+        torch.cuda.synchronize()
+        _attn_check(out, want)
+
+
 PIPE_VARIANTS = [(0, 3, 0, kv.KV_COPY_AUTO, kv.KV_COPY_AUTO),
                  (1, 2, 1, kv.KV_COPY_MEMCPY, kv.KV_COPY_MEMCPY),
                  (2, 4, 3, kv.KV_COPY_KERNEL, kv.KV_COPY_KERNEL),
