@@ -31,6 +31,7 @@
 #include <thread>
 #include <vector>
 
+#include "pacer.hpp"
 #include "plan.hpp"
 
 namespace {
@@ -221,12 +222,8 @@ struct kv_pipeline {
     std::vector<char> tail_img;
     std::vector<int64_t> tail_sector;
     const void *tail_region = nullptr, *tail_pageable = nullptr;  // host buffers the images were taken from
-    // Issue pacing (see kv_pipeline_run): the best transfer rate seen so far per direction (0 offload, 1 reload),
-    // bytes per second; 0 = nothing seen yet
-    double pace_rate[2] = {0.0, 0.0};
+    kvb::LinkRate link[2];       // issue pacing: the host link's rate per direction (0 offload, 1 reload)
     bool link_measured = false;
-    int pace_above[2] = {0, 0};        // consecutive windows that ran above pace_rate, and the lowest of them
-    double pace_low[2] = {0.0, 0.0};
 
     ~kv_pipeline()
     {
@@ -272,8 +269,8 @@ int measure_link_rates(kv_pipeline *q)
     std::lock_guard<std::mutex> g(g_link_mu);
     const int dev = q->device >= 0 && q->device < 64 ? q->device : 0;
     if (g_link_known[dev]) {
-        q->pace_rate[0] = std::max(q->pace_rate[0], g_link_rate[dev][0]);
-        q->pace_rate[1] = std::max(q->pace_rate[1], g_link_rate[dev][1]);
+        q->link[0].rate = std::max(q->link[0].rate, g_link_rate[dev][0]);
+        q->link[1].rate = std::max(q->link[1].rate, g_link_rate[dev][1]);
         q->link_measured = true;
         return KV_OK;
     }
@@ -296,16 +293,16 @@ int measure_link_rates(kv_pipeline *q)
             if (e == hipSuccess) e = hipEventSynchronize(e1);
             float ms = 0.f;
             if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-            if (e == hipSuccess && pass > 0 && ms > 0.f) q->pace_rate[dir] = std::max(q->pace_rate[dir], (double)bytes / (ms * 1e-3));
+            if (e == hipSuccess && pass > 0 && ms > 0.f) q->link[dir].rate = std::max(q->link[dir].rate, (double)bytes / (ms * 1e-3));
         }
     }
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
     (void)hipHostFree(pinned);
     if (e != hipSuccess) { kvb::set_hip_error((int)e); return KV_EHIP; }
-    if (q->pace_rate[0] > 0.0 && q->pace_rate[1] > 0.0) {
-        g_link_rate[dev][0] = q->pace_rate[0];
-        g_link_rate[dev][1] = q->pace_rate[1];
+    if (q->link[0].rate > 0.0 && q->link[1].rate > 0.0) {
+        g_link_rate[dev][0] = q->link[0].rate;
+        g_link_rate[dev][1] = q->link[1].rate;
         g_link_known[dev] = true;
     }
     return KV_OK;
@@ -735,53 +732,16 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         q->workers.push(tasks, n_tasks);
     };
 
-    // Issue pacing.  Commands that are queued back to back share the link, finish together and leave it idle
-    // while all of them are issued again (at 512 KiB and depth 3: 45 of 56.5 GB/s).  Spaced by one command's own
-    // link time they stay staggered: one completes while the others still move, and its successor is on its way
-    // before they end (54 GB/s; the spacing has to be right within a few percent: 0.97 of the link time gives 52,
-    // 1.06 gives 52.5, 0.85 gives 47).  The spacing is the previous command's bytes over the link rate measured when
-    // the process first ran a pipeline, or over the best rate a run has sustained since, if that is higher (measured
-    // between completions the thread really waited for, over windows of several queue depths): the rate only
-    // ratchets upward, so pacing never holds the commands below what the link has already shown.  Both copy
-    // engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
-    // (without a measured link rate -- a pipeline whose staging memory is too small to measure one -- nothing is paced:
-    // a rate taken from the run's own first windows could be a stalled one and hold everything back)
-    const bool paced = depth >= 2 && !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)) && q->pace_rate[offload_dir ? 0 : 1] > 0.0;
+    // Issue pacing (pacer.hpp): consecutive commands are queued no closer together than one command's own link time.
+    // Both copy engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
     const int pace_dir = offload_dir ? 0 : 1;
-    constexpr double kPaceHeadroom = 1.02;
-    const size_t pace_window = std::max<size_t>(16, 8 * (size_t)depth);
-    double pace_last_issue = -1.0, pace_last_bytes = 0.0;
-    double win_t0 = -1.0, win_bytes = 0.0;
-    size_t win_n = 0;
+    kvb::IssuePacer pacer(&q->link[pace_dir], !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)), depth);
     auto pace_issue = [&](uint64_t bytes) {   // call right before a command is queued
-        const double rate = q->pace_rate[pace_dir];
-        if (paced && rate > 0.0 && pace_last_issue >= 0.0) {
-            const double due = pace_last_issue + pace_last_bytes / (kPaceHeadroom * rate);
-            while (now_s() < due) __builtin_ia32_pause();
-        }
-        pace_last_issue = now_s();
-        pace_last_bytes = (double)bytes;
+        const double due = pacer.due();
+        while (now_s() < due) __builtin_ia32_pause();
+        pacer.issued(now_s(), bytes);
     };
-    auto pace_harvest = [&](uint64_t bytes, bool waited) {   // call when a completion is harvested
-        if (!paced) return;
-        if (win_t0 >= 0.0) { win_bytes += (double)bytes; ++win_n; }
-        if (!waited) return;                      // only a completion the thread waited for has an exact time
-        const double t = now_s();
-        if (win_t0 >= 0.0 && win_n >= pace_window && t > win_t0) {
-            // a window's rate carries a percent or two of timing noise: the rate moves up only after three windows
-            // in a row came out above it, and then to the lowest of the three
-            const double seen = win_bytes / (t - win_t0);
-            double &rate = q->pace_rate[pace_dir];
-            if (seen > rate) {
-                q->pace_low[pace_dir] = q->pace_above[pace_dir] == 0 ? seen : std::min(q->pace_low[pace_dir], seen);
-                if (++q->pace_above[pace_dir] >= 3) { rate = q->pace_low[pace_dir]; q->pace_above[pace_dir] = 0; }
-            } else {
-                q->pace_above[pace_dir] = 0;
-            }
-            win_t0 = -1.0;
-        }
-        if (win_t0 < 0.0) { win_t0 = t; win_bytes = 0.0; win_n = 0; }
-    };
+    auto pace_harvest = [&](uint64_t bytes, bool waited) { pacer.harvested(now_s(), bytes, waited); };
 
     // Chunk c owns ring entry c % NB.  Transfers are harvested in issue order; n_waited counts them.
     double host_wait_s = 0.0, harvest_wait_s = 0.0;
@@ -1052,7 +1012,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         stats->host_copy_wait_s = host_wait_s;
         stats->harvest_wait_s = harvest_wait_s;
         stats->n_traced = (uint32_t)n_traced;
-        stats->pace_GBps = q->pace_rate[pace_dir] / 1e9;
+        stats->pace_GBps = q->link[pace_dir].rate / 1e9;
         if (time_kernels && err == KV_OK) {
             for (size_t i = 0; i < timing_kind.size(); ++i) {
                 float ms = 0.f;
