@@ -32,6 +32,7 @@
 #include <vector>
 
 #include "pacer.hpp"
+#include "workers.hpp"
 #include "plan.hpp"
 
 namespace {
@@ -88,87 +89,6 @@ constexpr int kMaxCopyStreams = 4;
         }                                                  \
     }
 
-struct CopyTask {
-    void *dst;
-    const void *src;
-    size_t bytes;
-    std::atomic<int> *pending;
-};
-
-// Host threads of the page-cache path's memcpy hop.
-class Workers {
-public:
-    void start(int n)
-    {
-        if ((int)threads_.size() == n) return;
-        stop();
-        quit_ = false;
-        for (int i = 0; i < n; ++i) threads_.emplace_back([this] { loop(); });
-    }
-    void stop()
-    {
-        {
-            std::lock_guard<std::mutex> g(mu_);
-            quit_ = true;
-        }
-        cv_.notify_all();
-        for (auto &t : threads_) t.join();
-        threads_.clear();
-    }
-    // All pieces of one command under one lock; sleeping threads are woken only if there are any, and no
-    // more of them than there are pieces (the issuing thread pays for every wake-up call).
-    void push(const CopyTask *t, int n)
-    {
-        int wake = 0;
-        {
-            std::lock_guard<std::mutex> g(mu_);
-            for (int i = 0; i < n; ++i) q_.push_back(t[i]);
-            queued_.store((int)q_.size(), std::memory_order_release);
-            wake = std::min(n, sleeping_);
-        }
-        if (wake >= (int)threads_.size()) cv_.notify_all();
-        else for (int i = 0; i < wake; ++i) cv_.notify_one();
-    }
-    int size() const { return (int)threads_.size(); }
-    ~Workers() { stop(); }
-
-private:
-    void loop()
-    {
-        for (;;) {
-            CopyTask t;
-            // pieces arrive every few tens of microseconds while a call runs, and a sleeping thread takes about
-            // that long to wake: poll the queue length for a short while before going to sleep
-            for (int spin = 0; spin < kSpinsBeforeSleep && queued_.load(std::memory_order_acquire) == 0; ++spin) __builtin_ia32_pause();
-            {
-                std::unique_lock<std::mutex> g(mu_);
-                if (q_.empty() && !quit_) {
-                    ++sleeping_;
-                    cv_.wait(g, [this] { return quit_ || !q_.empty(); });
-                    --sleeping_;
-                }
-                if (q_.empty()) {
-                    if (quit_) return;
-                    continue;
-                }
-                t = q_.front();
-                q_.pop_front();
-                queued_.store((int)q_.size(), std::memory_order_release);
-            }
-            std::memcpy(t.dst, t.src, t.bytes);
-            t.pending->fetch_sub(1, std::memory_order_release);
-        }
-    }
-    std::vector<std::thread> threads_;
-    std::deque<CopyTask> q_;
-    std::mutex mu_;
-    std::condition_variable cv_;
-    bool quit_ = false;
-    int sleeping_ = 0;  // threads inside cv_.wait (under mu_)
-    std::atomic<int> queued_{0};  // queue length, readable without the lock
-    static constexpr int kSpinsBeforeSleep = 4000;  // roughly 50-100 us
-};
-
 struct Chunk {
     uint64_t host_off;   // byte offset in the LBA region (slba * sector) or in the arena
     uint64_t stage_off;  // byte offset inside the span's staging slot
@@ -212,7 +132,7 @@ struct kv_pipeline {
     std::vector<hipEvent_t> ev_done;            // per staging slot and copy stream
     std::vector<Entry> ring;                    // per in-flight command
     std::vector<hipEvent_t> timing;             // pairs
-    Workers workers;
+    kvb::Workers workers;
     // decode append: pinned landing buffer for the packed rows, and per (tensor, sequence) the image of
     // the last partly filled sector (so that only the first append after an offload has to read it back)
     void *seq_off_dev = nullptr;  // per-sequence element offsets inside an extent image (attention from extents)
@@ -720,13 +640,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         int pieces = (int)std::min<size_t>((size_t)pieces_max, std::max<size_t>(1, bytes / (256 * 1024)));
         e.pending.store(pieces, std::memory_order_release);
         const size_t step = kvb::round_up(kvb::ceil_div(bytes, (uint64_t)pieces), 4096);
-        CopyTask tasks[64];
+        kvb::CopyTask tasks[64];
         size_t off = 0;
         int n_tasks = 0;
         for (int i = 0; i < pieces; ++i) {
             const size_t n = off < bytes ? std::min(step, bytes - off) : 0;
             if (n == 0) { e.pending.fetch_sub(1, std::memory_order_release); continue; }
-            tasks[n_tasks++] = CopyTask{(char *)dst + off, (const char *)src + off, n, &e.pending};
+            tasks[n_tasks++] = kvb::CopyTask{(char *)dst + off, (const char *)src + off, n, &e.pending};
             off += n;
         }
         q->workers.push(tasks, n_tasks);
