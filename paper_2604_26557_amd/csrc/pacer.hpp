@@ -30,15 +30,20 @@ public:
     static constexpr double kHeadroom = 1.02;
 
     IssuePacer(LinkRate *link, bool enabled, int depth)
-        : link_(link), on_(enabled && depth >= 2 && link->rate > 0.0), window_(std::max<size_t>(16, 8 * (size_t)depth))
+        : link_(link), on_(enabled && depth >= 2 && link->rate > 0.0), depth_((size_t)std::max(depth, 1)),
+          window_(std::max<size_t>(16, 8 * (size_t)depth))
     {
     }
     bool enabled() const { return on_; }
-    // Earliest time at which the next command may be queued (a time in the past: no wait).
-    double due() const
+    // Earliest time at which the next command may be queued (a time in the past: no wait), with `in_flight` commands
+    // outstanding.  One free slot is the steady state (a command has just completed): the spacing is the previous
+    // command's link time.  Two or more free slots mean the queue has fallen behind (a stall on the host, the start
+    // of a call): at the link's own rate it would never fill up again, so the spacing is halved until one slot is left.
+    double due(size_t in_flight) const
     {
         if (!on_ || last_issue_ < 0.0) return -1.0;
-        return last_issue_ + last_bytes_ / (kHeadroom * link_->rate);
+        const double tau = last_bytes_ / (kHeadroom * link_->rate);
+        return last_issue_ + (in_flight + 2 <= depth_ ? 0.5 * tau : tau);
     }
     // A command of `bytes` is being queued at time `now`.
     void issued(double now, uint64_t bytes)
@@ -68,7 +73,7 @@ public:
 private:
     LinkRate *link_;
     bool on_;
-    size_t window_;
+    size_t depth_, window_;
     double last_issue_ = -1.0, last_bytes_ = 0.0;
     double win_t0_ = -1.0, win_bytes_ = 0.0;
     size_t win_n_ = 0;

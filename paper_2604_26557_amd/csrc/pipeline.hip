@@ -652,12 +652,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         q->workers.push(tasks, n_tasks);
     };
 
+    const size_t in_flight_max = offload_dir && !d2h_kernel ? std::min<size_t>((size_t)depth, 4) : (size_t)depth;
     // Issue pacing (pacer.hpp): consecutive commands are queued no closer together than one command's own link time.
     // Both copy engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
     const int pace_dir = offload_dir ? 0 : 1;
-    kvb::IssuePacer pacer(&q->link[pace_dir], !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)), depth);
-    auto pace_issue = [&](uint64_t bytes) {   // call right before a command is queued
-        const double due = pacer.due();
+    kvb::IssuePacer pacer(&q->link[pace_dir], !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)), (int)in_flight_max);
+    auto pace_issue = [&](uint64_t bytes, size_t in_flight) {   // call right before a command is queued
+        const double due = pacer.due(in_flight);
         while (now_s() < due) __builtin_ia32_pause();
         pacer.issued(now_s(), bytes);
     };
@@ -665,10 +666,12 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
 
     // Chunk c owns ring entry c % NB.  Transfers are harvested in issue order; n_waited counts them.
     double host_wait_s = 0.0, harvest_wait_s = 0.0;
-    auto harvest_until = [&](size_t upto) -> int {  // transfers of chunks [0, upto) are complete
+    // Harvest the transfers of chunks [0, upto); block = false: only those that have already completed.
+    auto harvest_until = [&](size_t upto, bool block = true) -> int {
         while (n_waited < upto) {
             bool waited = false;
             if (hipEventQuery(q->ring[n_waited % NB].ev) != hipSuccess) {
+                if (!block) { (void)hipGetLastError(); break; }
                 const double t0 = now_s();
                 KV_HIP(hipEventSynchronize(q->ring[n_waited % NB].ev));
                 harvest_wait_s += now_s() - t0;
@@ -685,8 +688,10 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         }
         return KV_OK;
     };
-    // At most `depth` transfers outstanding: the oldest is harvested before chunk c is issued.
-    auto transfer_slot = [&](size_t c) -> int { return c >= (size_t)depth ? harvest_until(c + 1 - (size_t)depth) : KV_OK; };
+    // At most `depth` transfers outstanding: the oldest is harvested before chunk c is issued.  The rule is an upper
+    // bound, and D2H hipMemcpyAsync commands use less of it: each runs as a wide-grid kernel of the runtime's, and more
+    // than four of those at once get in each other's way (2 MiB commands at depth 8: 40 GB/s, at depth 4: 56).
+    auto transfer_slot = [&](size_t c) -> int { return c >= in_flight_max ? harvest_until(c + 1 - in_flight_max) : KV_OK; };
     // Ring entry (and bounce slot) of chunk c is free once chunk c - NB has left it, host copy included.
     auto entry_free = [&](size_t c) -> int {
         if (c < NB) return KV_OK;
@@ -760,7 +765,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 KV_HIP_BRK(hipStreamWaitEvent(st, q->ev_ready[slot], 0));
                 used |= 1u << s;
             }
-            pace_issue(ch.bytes);
+            if ((err = harvest_until(c, false)) != KV_OK) break;   // whatever has completed: the pacer counts what is really outstanding
+            pace_issue(ch.bytes, c - n_waited);
             if (sp.path == KV_PATH_DIRECT) {
                 KV_HIP_BRK(issue_copy(host_ptr(ch), img + ch.stage_off, ch.bytes, true, st, e.ev));
             } else {
@@ -817,11 +823,13 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 used |= 1u << s;
             }
             if (sp.path == KV_PATH_DIRECT) {
-                pace_issue(ch.bytes);
+                if ((err = harvest_until(ci, false)) != KV_OK) break;
+                pace_issue(ch.bytes, ci - n_waited);
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, host_ptr(ch), ch.bytes, false, st, e.ev));
             } else {
                 host_wait_s += spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
-                pace_issue(ch.bytes);
+                if ((err = harvest_until(ci, false)) != KV_OK) break;
+                pace_issue(ch.bytes, ci - n_waited);
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st, e.ev));
             }
             trace_issue(ci);

@@ -16,11 +16,12 @@ int main(int argc, char **argv)
     kvb::IssuePacer p(&link, true, depth);
     printf("enabled %d\n", (int)p.enabled());
     // first command: nothing to wait for
-    printf("due_first %.13f\n", p.due());
+    printf("due_first %.13f\n", p.due(0));
     p.issued(1.0, bytes);
-    printf("due_second %.13f\n", p.due());
-    p.issued(p.due(), 2 * bytes);
-    printf("due_third %.13f\n", p.due());
+    printf("due_second %.13f\n", p.due(depth - 1));
+    p.issued(p.due(depth - 1), 2 * bytes);
+    printf("due_third %.13f\n", p.due(depth - 1));
+    printf("due_third_behind %.13f\n", p.due(depth >= 2 ? depth - 2 : 0));
     // a link that sustains true_rate: completions the thread waited for arrive every bytes / true_rate
     double t = 2.0;
     for (int w = 0; w < 12; ++w) {

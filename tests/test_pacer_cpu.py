@@ -35,6 +35,8 @@ def test_spacing_is_the_previous_commands_link_time(harness):
     assert float(r["due_second"][0][0]) == pytest.approx(1.0 + tau, abs=1e-12 * 2)
     # the second command had twice the bytes: the third waits twice as long after it
     assert float(r["due_third"][0][0]) == pytest.approx(1.0 + tau + 2 * tau, abs=1e-12 * 2)
+    # two free slots (the queue has fallen behind): half the spacing, so that it fills up again
+    assert float(r["due_third_behind"][0][0]) == pytest.approx(1.0 + tau + tau, abs=1e-12 * 2)
 
 
 @pytest.mark.parametrize("depth", [2, 3, 8])
