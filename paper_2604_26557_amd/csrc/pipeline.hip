@@ -27,6 +27,7 @@
 #include <condition_variable>
 #include <cstring>
 #include <deque>
+#include <functional>
 #include <mutex>
 #include <thread>
 #include <vector>
@@ -657,10 +658,21 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // Both copy engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
     const int pace_dir = offload_dir ? 0 : 1;
     kvb::IssuePacer pacer(&q->link[pace_dir], !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)), (int)in_flight_max);
-    auto pace_issue = [&](uint64_t bytes, size_t in_flight) {   // call right before a command is queued
-        const double due = pacer.due(in_flight);
-        while (now_s() < due) __builtin_ia32_pause();
+    // forward declaration of the harvest (defined below): the pacer polls it while it waits
+    std::function<int(size_t, bool)> harvest_ready;
+    // Call right before command c is queued: waits until the pacer lets it go.  While it waits it harvests, without
+    // blocking, whatever has completed, so that the pacer counts what is really outstanding (this costs nothing
+    // when the host is the bottleneck: then there is no wait).
+    auto pace_issue = [&](uint64_t bytes, size_t c) -> int {
+        if (pacer.enabled()) {
+            while (now_s() < pacer.due(c - n_waited)) {
+                const int r = harvest_ready(c, false);
+                if (r != KV_OK) return r;
+                __builtin_ia32_pause();
+            }
+        }
         pacer.issued(now_s(), bytes);
+        return KV_OK;
     };
     auto pace_harvest = [&](uint64_t bytes, bool waited) { pacer.harvested(now_s(), bytes, waited); };
 
@@ -691,6 +703,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // At most `depth` transfers outstanding: the oldest is harvested before chunk c is issued.  The rule is an upper
     // bound, and D2H hipMemcpyAsync commands use less of it: each runs as a wide-grid kernel of the runtime's, and more
     // than four of those at once get in each other's way (2 MiB commands at depth 8: 40 GB/s, at depth 4: 56).
+    harvest_ready = harvest_until;
     auto transfer_slot = [&](size_t c) -> int { return c >= in_flight_max ? harvest_until(c + 1 - in_flight_max) : KV_OK; };
     // Ring entry (and bounce slot) of chunk c is free once chunk c - NB has left it, host copy included.
     auto entry_free = [&](size_t c) -> int {
@@ -765,8 +778,7 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 KV_HIP_BRK(hipStreamWaitEvent(st, q->ev_ready[slot], 0));
                 used |= 1u << s;
             }
-            if ((err = harvest_until(c, false)) != KV_OK) break;   // whatever has completed: the pacer counts what is really outstanding
-            pace_issue(ch.bytes, c - n_waited);
+            if ((err = pace_issue(ch.bytes, c)) != KV_OK) break;
             if (sp.path == KV_PATH_DIRECT) {
                 KV_HIP_BRK(issue_copy(host_ptr(ch), img + ch.stage_off, ch.bytes, true, st, e.ev));
             } else {
@@ -823,13 +835,11 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
                 used |= 1u << s;
             }
             if (sp.path == KV_PATH_DIRECT) {
-                if ((err = harvest_until(ci, false)) != KV_OK) break;
-                pace_issue(ch.bytes, ci - n_waited);
+                if ((err = pace_issue(ch.bytes, ci)) != KV_OK) break;
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, host_ptr(ch), ch.bytes, false, st, e.ev));
             } else {
                 host_wait_s += spin_until_zero(e.pending);  // the arena bytes are in the bounce slot
-                if ((err = harvest_until(ci, false)) != KV_OK) break;
-                pace_issue(ch.bytes, ci - n_waited);
+                if ((err = pace_issue(ch.bytes, ci)) != KV_OK) break;
                 KV_HIP_BRK(issue_copy(img + ch.stage_off, bounce_ptr(ci), ch.bytes, false, st, e.ev));
             }
             trace_issue(ci);
