@@ -398,7 +398,7 @@ def main():
         attn_us, attn_n = kstat(kv.KV_KERNEL_ATTN_PARTIAL, 1)
         per_t_pack = pack_n / (2 * L * args.steps)
         per_t_unpack = max(unpack_n, 1) / (2 * L * args.steps)
-        where = "inside the pipeline steps (DMA in flight, GPU otherwise idle)"
+        where = "inside the pipeline steps (chunk commands in flight next to the kernels)"
         res["rooflines_in_pipeline"] = [
             roof("kv_layout_kernel<pack>", pack_us, (tensor_payload + tensor_image) / per_t_pack, where),
             roof("kv_layout_kernel<unpack>", unpack_us, 2 * tensor_payload / per_t_unpack, where),

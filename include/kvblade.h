@@ -156,8 +156,9 @@ typedef struct kv_attn_args {
 #define KV_PIPE_SERIALIZE 2u    /* run every stage (kernel, chunk transfer, host copy) to completion before
                                    the next starts: the no-overlap reference for the overlap fraction */
 
-#define KV_COPY_AUTO 0   /* the faster of the two as measured: H2D the copy kernel; D2H the copy kernel for commands
-                            below 2 MiB, hipMemcpyAsync from 2 MiB on */
+#define KV_COPY_AUTO 0   /* by measurement: the copy kernel for small commands (H2D up to 1 MiB, D2H below 1 MiB),
+                            hipMemcpyAsync for larger ones (H2D on the SDMA engines: a copy kernel slows the other
+                            wavefronts of the compute units it runs on) */
 #define KV_COPY_MEMCPY 1 /* hipMemcpyAsync per chunk command */
 #define KV_COPY_KERNEL 2 /* the library's copy kernel per chunk command */
 

@@ -13,11 +13,11 @@
 // Streams: the caller's own for kernels and up to four for copies (chunk c goes to copy stream c mod n, so the
 // start-up and tail of one transfer hide behind the next); events order pack -> D2H and
 // H2D -> unpack -> attention and guard staging-slot reuse.  All streams keep the default priority.
-// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): H2D commands of every size, and D2H
-// commands below 2 MiB, move fastest as this file's own copy kernel over three streams (its completion event
-// rides on the dispatch: the runtime's per-command cost dominates copies of a few hundred KiB); D2H commands
-// from 2 MiB on as hipMemcpyAsync over up to four streams.  Both engines are options.  Commands are issued
-// no closer together than one command's own link time, which keeps them from finishing in lockstep.
+// Measured on MI355X (PCIe Gen5 x16, ~56.7 GB/s with 64 MiB copies): small commands (H2D up to 1 MiB, D2H
+// below 1 MiB) move fastest as this file's own copy kernel over three streams (its completion event rides on
+// the dispatch: the runtime's per-command cost dominates copies of a few hundred KiB); larger ones go through
+// hipMemcpyAsync over up to four streams.  Both engines are options.  Commands are issued no closer together
+// than one command's own link time, which keeps them from finishing in lockstep.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
@@ -486,13 +486,21 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     if (d2h_mode < KV_COPY_AUTO || d2h_mode > KV_COPY_KERNEL || h2d_mode < KV_COPY_AUTO || h2d_mode > KV_COPY_KERNEL)
         return KV_EINVAL;
     // Engine defaults by measurement inside the paced pipeline (8B shape at 4K / 32K, ragged paged batch, Gemma
-    // shape; three alternations per variant in one process): H2D is fastest as the copy kernel over three streams
-    // at every command size (32K shape: reload + attention 55.6-56.2 GB/s against 53.5-54.1 with hipMemcpyAsync;
-    // Gemma shape 57.2 against 56.0-56.9); D2H as the copy kernel over three streams below 2 MiB (512 KiB commands:
-    // 48 against 42 GB/s; 1 MiB: 52.9 steady against 50.7-53.4), as hipMemcpyAsync over up to four streams from
-    // 2 MiB on (2 MiB: 54.4-55.9 against 54.0-54.7; 8 MiB: 55.9-56.8 against 55.2-55.4; the runtime runs those
-    // copies as a kernel of its own).  Eight workgroups per command in both directions: 16, 32 and 64 lose
-    // 2, 4 and 7-14 GB/s on the reload side, where the unpack and attention kernels run next to the copies.
+    // shape; three alternations per variant in one process).
+    //  * H2D: the copy kernel over three streams for commands up to 1 MiB (512 KiB: 50 GB/s against 40 with
+    //    hipMemcpyAsync), hipMemcpyAsync (SDMA engines) over up to four streams above.  The copy kernel would move
+    //    2 and 8 MiB commands faster too (reload + attention 55.6-56.2 against 53.5-54.4 GB/s at the 32K shape, 57.2
+    //    against 56.0-56.9 at the Gemma shape), but a compute unit that hosts a copy workgroup serves the loads of its
+    //    other wavefronts behind the copy's PCIe reads: with it the unpack of a layer takes 135 instead of 68 us
+    //    and the decode attention 127 instead of 42 us inside the pipeline (46 and 26 us with nothing else running).
+    //    Where SDMA keeps up, the kernels that run next to the transfers -- here unpack and attention, in a
+    //    serving system the model's own layers -- keep the compute units to themselves.
+    //  * D2H: the copy kernel over three streams below 1 MiB (512 KiB: 48 against 42 GB/s), hipMemcpyAsync over up
+    //    to four streams from 1 MiB on (1 MiB: 50.7-53.4 against a steady 52.9; 2 MiB: 54.4-55.9 against 54.0-54.7;
+    //    8 MiB: 55.9-56.8 against 55.2-55.4).  The runtime runs those copies as a kernel of its own, which disturbs
+    //    the pack next to it less than this file's copy kernel does (57-69 against 132-153 us per pack).
+    //  * Eight workgroups per copy command in both directions: 16, 32 and 64 lose 2, 4 and 7-14 GB/s on the
+    //    reload side.
     uint64_t cmd_bytes = (chunk_tokens > 0 ? (uint64_t)chunk_tokens : (uint64_t)p->chunk_tokens) * p->row_bytes;
     uint64_t cmd_limit = UINT64_MAX;  // Eq. 7 on the caller's transfer-size limit
     if (opts && opts->max_cmd_bytes) {
@@ -500,8 +508,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
         if (cmd_limit == 0) return KV_EINVAL;
         cmd_bytes = std::min(cmd_bytes, cmd_limit);
     }
-    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && cmd_bytes < (2ull << 20));
-    const bool h2d_kernel = h2d_mode != KV_COPY_MEMCPY;
+    const bool d2h_kernel = d2h_mode == KV_COPY_KERNEL || (d2h_mode == KV_COPY_AUTO && cmd_bytes < (1ull << 20));
+    const bool h2d_kernel = h2d_mode == KV_COPY_KERNEL || (h2d_mode == KV_COPY_AUTO && cmd_bytes <= (1ull << 20));
     const int order_pc = opts ? opts->order_pagecache : KV_ORDER_CROSS;
     const int order_direct = opts ? opts->order_direct : KV_ORDER_CROSS;
     if ((order_pc != KV_ORDER_CROSS && order_pc != KV_ORDER_INTRA) ||
