@@ -38,6 +38,17 @@ def test_header_symbols_exported():
     assert lib.kv_abi_sizeof(7) == kv.C.sizeof(kv.kv_pipe_stats_t) and lib.kv_abi_sizeof(99) == 0
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own, with every struct usable by value."""
+    import subprocess
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "kvblade.h"\n'
+                   'int main(void) { kv_plan_desc_t d; kv_view_t v; kv_pipe_opts_t o; kv_pipe_stats_t s; kv_chunk_trace_t t;\n'
+                   '  (void)d; (void)v; (void)o; (void)s; (void)t; return kv_abi_version() < 0; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           "-c", str(src), "-o", str(tmp_path / "hdr.o")])
+
+
 @pytest.mark.parametrize("idx", range(5))
 def test_plan_matches_oracle_all_configs(idx):
     cfg = W.CONFIGS[idx]
