@@ -665,7 +665,8 @@ extern "C" int kv_pipeline_run(kv_plan_t *p, int dir, int layer_begin, int layer
     // Issue pacing (pacer.hpp): consecutive commands are queued no closer together than one command's own link time.
     // Both copy engines are paced: with hipMemcpyAsync commands of 2 and 8 MiB it gains 2-4 % as well.
     const int pace_dir = offload_dir ? 0 : 1;
-    kvb::IssuePacer pacer(&q->link[pace_dir], !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)), (int)in_flight_max);
+    kvb::IssuePacer pacer(&q->link[pace_dir], !serialize && !(opts && (opts->flags & KV_PIPE_NO_PACING)), (int)in_flight_max,
+                          (offload_dir ? d2h_kernel : h2d_kernel) ? 1.0 : 0.5);
     // forward declaration of the harvest (defined below): the pacer polls it while it waits
     std::function<int(size_t, bool)> harvest_ready;
     // Call right before command c is queued: waits until the pacer lets it go.  While it waits it harvests, without

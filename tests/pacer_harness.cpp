@@ -22,6 +22,12 @@ int main(int argc, char **argv)
     p.issued(p.due(depth - 1), 2 * bytes);
     printf("due_third %.13f\n", p.due(depth - 1));
     printf("due_third_behind %.13f\n", p.due(depth >= 2 ? depth - 2 : 0));
+    {   // the same two commands with no catch-up (factor 1): two free slots do not shorten the spacing
+        kvb::IssuePacer pk(&link, true, depth, 1.0);
+        pk.issued(1.0, bytes);
+        pk.issued(pk.due(depth - 1), 2 * bytes);
+        printf("due_third_behind_no_catch_up %.13f\n", pk.due(depth >= 2 ? depth - 2 : 0));
+    }
     // a link that sustains true_rate: completions the thread waited for arrive every bytes / true_rate
     double t = 2.0;
     for (int w = 0; w < 12; ++w) {

@@ -37,6 +37,8 @@ def test_spacing_is_the_previous_commands_link_time(harness):
     assert float(r["due_third"][0][0]) == pytest.approx(1.0 + tau + 2 * tau, abs=1e-12 * 2)
     # two free slots (the queue has fallen behind): half the spacing, so that it fills up again
     assert float(r["due_third_behind"][0][0]) == pytest.approx(1.0 + tau + tau, abs=1e-12 * 2)
+    # the copy-kernel engine's setting: no catch-up
+    assert float(r["due_third_behind_no_catch_up"][0][0]) == pytest.approx(1.0 + tau + 2 * tau, abs=1e-12 * 2)
 
 
 @pytest.mark.parametrize("depth", [2, 3, 8])
