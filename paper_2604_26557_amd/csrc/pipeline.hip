@@ -24,9 +24,7 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
-#include <condition_variable>
 #include <cstring>
-#include <deque>
 #include <functional>
 #include <mutex>
 #include <thread>
